@@ -1,0 +1,150 @@
+/*
+ * libmeft -- the sparse-adapter layer of MEFT (Memory-Efficient Fine-Tuning through Sparse
+ * Adapter) for one AMD MI355X (gfx950).  Plain C ABI: pointers and sizes only.
+ *
+ * The layer (paper: Section 3.1 "Sparse Activation", Section 3.2 "Key-Experts Mechanism",
+ * Algorithm 1 "MEFT FFN Layer", evaluated per token):
+ *
+ *   p[t,b]   = sum_c Wg[b,c] h[t,c] (+ bias[b])                 router score, Eq. 5 (no softmax)
+ *   tau_t    = the top_e blocks (key experts) with the largest p[t,.]
+ *   sc[t,j]  = sum_c h[t,c] K[j,c]   for every neuron j of the blocks in tau_t       Eq. 6
+ *   I_t      = the top_k of those neurons with the largest sc[t,j]                    Eq. 1
+ *   out[t,:] = sum_{j in I_t} max(sc[t,j],0) V[j,:]                                   Eq. 4
+ *
+ * and its backward, in which only the activated neurons receive gradient (last paragraph of
+ * Section 3.1):
+ *
+ *   ds[t,j]  = (dOut[t,:] . V[j,:])  if sc[t,j] > 0 else 0
+ *   dh[t,:]  = sum_{j in I_t} ds[t,j] K[j,:]
+ *   dK[j,:]  = sum_{t: j in I_t} ds[t,j] h[t,:]      dV[j,:] = sum_{t: j in I_t} max(sc[t,j],0) dOut[t,:]
+ *
+ * Naming: T tokens, hidden size d, N = n_blocks*block_size adapter neurons (the paper's r), K[N,d]
+ * the keys (row j = column j of the paper's W_A), V[N,d] the values (row j of W_B), Wg[n_blocks,d]
+ * the router.  Block b owns the contiguous neurons [b*block_size, (b+1)*block_size).
+ * Ties in both selections go to the lower index; +0 and -0 tie.  The router score only selects
+ * (no gate multiply), so there is no router gradient.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller, row-major, contiguous, 16-byte
+ *    aligned.  With MEFT_FLAG_HOST_KV set, K, V, dK, dV are pinned HOST pointers instead.
+ *  - `ws` is a device workspace of at least meft_workspace_bytes(shape) bytes, 256-byte aligned,
+ *    owned by the caller; its contents are scratch and carry nothing from call to call.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
+ *    it; the library never synchronises the stream, allocates no device memory per call and keeps
+ *    no state between calls.  Calls that share a workspace must be ordered on one stream.
+ *  - Arguments are validated on the host before anything is enqueued; a non-zero status means
+ *    nothing was enqueued.  Faults that happen on the device later surface at the caller's next
+ *    synchronisation.  Inputs must be finite (the ordering of NaN is unspecified).
+ *  - dtype applies to h, Wg, K, V, out, dOut, dh, dK, dV.  Accumulation is fp32; results are rounded
+ *    once (to nearest even) when stored.
+ */
+#ifndef MEFT_H
+#define MEFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MEFT_OK = 0,
+  MEFT_ERR_INVALID_ARG = 1, /* NULL pointer, misaligned pointer, inconsistent or non-positive sizes */
+  MEFT_ERR_UNSUPPORTED = 2, /* a valid problem this build has no kernel for (see limits below)      */
+  MEFT_ERR_WORKSPACE = 3,   /* ws is NULL, misaligned or smaller than meft_workspace_bytes()        */
+  MEFT_ERR_DEVICE = 4       /* a HIP call (launch, copy) reported an error                          */
+} meft_status;
+
+typedef enum { MEFT_F32 = 0, MEFT_BF16 = 1 } meft_dtype;
+
+enum { MEFT_FLAG_HOST_KV = 1u }; /* K, V (and dK, dV) are pinned-host pointers */
+
+/*
+ * Problem shape.  Requirements (else MEFT_ERR_INVALID_ARG):
+ *   T >= 0; d, n_blocks, block_size >= 1; N == n_blocks*block_size; 1 <= top_e <= n_blocks;
+ *   1 <= top_k <= top_e*block_size; T*top_k and T*top_e*block_size below 2^31; activation == 0.
+ * Limits of this build (else MEFT_ERR_UNSUPPORTED):
+ *   d a multiple of 8 and at most 16384; top_e*block_size at most 12288; n_blocks at most 16384.
+ */
+typedef struct {
+  int32_t T, d, N, n_blocks, block_size;
+  int32_t top_e, top_k;
+  int32_t dtype;      /* meft_dtype */
+  int32_t activation; /* 0 = ReLU, the paper's choice and the only value */
+  uint32_t flags;
+} meft_shape;
+
+/* Bytes of workspace that any of the three calls below needs for this shape (0 if the shape is
+ * invalid or unsupported). */
+size_t meft_workspace_bytes(const meft_shape* shape);
+
+/* MEFT_OK if the shape is valid and supported, else the status the entry points would return. */
+meft_status meft_check_shape(const meft_shape* shape);
+
+const char* meft_status_string(meft_status status);
+
+/*
+ * Router scores and expert selection (Section 3.2, Eq. 5 and the top-K that follows it;
+ * Algorithm 1, the two statements at the head of the token loop).
+ *   h           [T, d]          in   hidden states
+ *   Wg          [n_blocks, d]   in   router
+ *   bias        [n_blocks] f32  in   added to the score, or NULL (NULL is the paper's router)
+ *   block_idx   [T, top_e] i32  out  chosen blocks, ordered by (score descending, id ascending)
+ *   block_score [T, top_e] f32  out  their scores, or NULL
+ */
+meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, const float* bias,
+                       int32_t* block_idx, float* block_score, void* ws, size_t ws_bytes,
+                       void* stream);
+
+/*
+ * Key scores inside the chosen blocks, top-k neuron selection, gather of the selected value rows
+ * and the activation-weighted sum (Section 3.2 Eq. 6-7; Section 3.1 Eq. 1-4; Algorithm 1, inner
+ * loop, TopK and the returned adapter term).
+ *   h         [T, d]           in
+ *   K, V      [N, d]           in   keys, values
+ *   block_idx [T, top_e] i32   in   distinct block ids per token, any order (as meft_route writes)
+ *   out       [T, d]           out  adapter output (the frozen FFN term is the caller's)
+ *   idx       [T, top_k] i32   out  selected neuron ids (global), distinct per token, ascending
+ *   act       [T, top_k] f32   out  max(score, 0) of idx[t, i]
+ * A block id outside [0, n_blocks) or repeated within a token is a caller error; such ids are
+ * clamped into range so that no access leaves the tensors, and the results for that token are
+ * unspecified.
+ */
+meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* K, const void* V,
+                            const int32_t* block_idx, void* out, int32_t* idx, float* act, void* ws,
+                            size_t ws_bytes, void* stream);
+
+/*
+ * Backward of meft_sparse_fwd for the saved selection (Section 3.1, last paragraph).
+ *   h, K, V             in   as in the forward
+ *   idx, act            in   as the forward wrote them (any order inside a token; ids distinct
+ *                            per token and in [0, N))
+ *   dOut   [T, d]       in   gradient of the loss with respect to out
+ *   dh     [T, d]       out  or NULL
+ *   dK, dV [N, d]       out  ONLY the rows listed in `touched` are written (overwritten, not
+ *                            accumulated); every other row is neither read nor written
+ *   touched [min(N, T*top_k)] i32  out  ascending ids of the neurons some token selected
+ *   n_touched [1] i32   out  their number (device memory, like touched)
+ * Pairs of one neuron are summed in ascending token order, so results are identical run to run.
+ * Ids outside [0, N) are clamped into range (caller error, results unspecified).
+ */
+meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* K, const void* V,
+                            const int32_t* idx, const float* act, const void* dOut, void* dh,
+                            void* dK, void* dV, int32_t* touched, int32_t* n_touched, void* ws,
+                            size_t ws_bytes, void* stream);
+
+/*
+ * Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every kernel
+ * the library launches is bracketed by HIP events on the caller's stream.  meft_profile_read
+ * synchronises those events and returns, for up to `cap` distinct kernel names in first-launch
+ * order, the name, the number of launches and the summed milliseconds since the last
+ * meft_profile_enable(1).  Returns the number of entries written.  Host memory; not thread-safe.
+ */
+void meft_profile_enable(int on);
+int meft_profile_read(const char** names, int32_t* launches, float* total_ms, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEFT_H */

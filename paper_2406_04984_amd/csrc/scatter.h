@@ -1,0 +1,171 @@
+// Backward weight gradients without floating-point atomics: the (token, neuron) pairs are grouped
+// by neuron (counting sort; integer atomics only decide positions, and every group is then put in
+// ascending pair order, i.e. ascending token), and one workgroup per touched neuron sums its
+// group in that fixed order:  dV[j,:] = sum act * dOut[t,:],  dK[j,:] = sum ds * h[t,:].
+// Only touched rows are written.
+#pragma once
+#include "common.h"
+
+namespace meft {
+
+__global__ void fill_i32_kernel(int32_t* __restrict__ p, size_t n, int32_t v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// cnt[j] += 1 for every pair
+__global__ void pair_count_kernel(const int32_t* __restrict__ idx, int P, int N, int32_t* __restrict__ cnt) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < P) atomicAdd(&cnt[clampi(idx[p], 0, N - 1)], 1);
+}
+
+// seg_off = exclusive scan of cnt; touched = ascending ids with cnt > 0.  One workgroup of 1024.
+__global__ __launch_bounds__(1024) void pair_scan_kernel(const int32_t* __restrict__ cnt, int N,
+                                                         int32_t* __restrict__ seg_off,
+                                                         int32_t* __restrict__ touched,
+                                                         int32_t* __restrict__ n_touched) {
+  __shared__ int s_c[16], s_f[16];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int chunk = (N + 1023) / 1024;
+  const int j0 = min(N, tid * chunk), j1 = min(N, j0 + chunk);
+  int c = 0, f = 0;
+  for (int j = j0; j < j1; ++j) { const int v = cnt[j]; c += v; f += v > 0; }
+  const int ci = wave_incl_scan(c), fi = wave_incl_scan(f);
+  if (lane == 63) { s_c[w] = ci; s_f[w] = fi; }
+  __syncthreads();
+  int cb = 0, fb = 0;
+  for (int i = 0; i < w; ++i) { cb += s_c[i]; fb += s_f[i]; }
+  int off = cb + ci - c, nt = fb + fi - f;
+  for (int j = j0; j < j1; ++j) {
+    const int v = cnt[j];
+    seg_off[j] = off;
+    off += v;
+    if (v > 0) touched[nt++] = j;
+  }
+  if (tid == 1023) { seg_off[N] = off; *n_touched = nt; }
+}
+
+// unordered placement of the pairs into their neuron's segment
+__global__ void pair_fill_kernel(const int32_t* __restrict__ idx, int P, int N,
+                                 const int32_t* __restrict__ seg_off, int32_t* __restrict__ cursor,
+                                 int32_t* __restrict__ pair_list) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= P) return;
+  const int j = clampi(idx[p], 0, N - 1);
+  const int pos = atomicAdd(&cursor[j], 1);
+  pair_list[seg_off[j] + pos] = p;
+}
+
+// puts every segment in ascending pair order: rank of an entry = number of smaller entries of the
+// segment (pair ids are distinct).  One workgroup per touched neuron.
+__global__ __launch_bounds__(256) void seg_sort_kernel(const int32_t* __restrict__ touched,
+                                                       const int32_t* __restrict__ n_touched,
+                                                       const int32_t* __restrict__ seg_off,
+                                                       const int32_t* __restrict__ pair_list,
+                                                       int32_t* __restrict__ pair_sorted) {
+  constexpr int LMAX = 2048;
+  __shared__ int32_t s_p[LMAX];
+  const int u = blockIdx.x;
+  if (u >= *n_touched) return;
+  const int j = touched[u];
+  const int o = seg_off[j], L = seg_off[j + 1] - o;
+  const int32_t* src = pair_list + o;
+  if (L <= LMAX) {
+    for (int i = threadIdx.x; i < L; i += 256) s_p[i] = src[i];
+    __syncthreads();
+    for (int i = threadIdx.x; i < L; i += 256) {
+      const int v = s_p[i];
+      int r = 0;
+      for (int z = 0; z < L; ++z) r += s_p[z] < v;
+      pair_sorted[o + r] = v;
+    }
+  } else {
+    for (int i = threadIdx.x; i < L; i += 256) {
+      const int v = src[i];
+      int r = 0;
+      for (int z = 0; z < L; ++z) r += src[z] < v;
+      pair_sorted[o + r] = v;
+    }
+  }
+}
+
+// dV[j,:] and dK[j,:] of one touched neuron, pairs summed in ascending pair order.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void seg_reduce_kernel(const int32_t* __restrict__ touched,
+                                                         const int32_t* __restrict__ n_touched,
+                                                         const int32_t* __restrict__ seg_off,
+                                                         const int32_t* __restrict__ pair_sorted,
+                                                         const float* __restrict__ act,
+                                                         const float* __restrict__ ds,
+                                                         const T* __restrict__ h, const T* __restrict__ dOut,
+                                                         int d, int k, T* __restrict__ dK,
+                                                         T* __restrict__ dV) {
+  const int u = blockIdx.x;
+  if (u >= *n_touched) return;
+  const int j = touched[u];
+  const int o = seg_off[j], L = seg_off[j + 1] - o;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  float aK[NV][8], aV[NV][8];
+#pragma unroll
+  for (int v = 0; v < NV; ++v)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { aK[v][c] = 0.f; aV[v][c] = 0.f; }
+  constexpr int U = 2;
+  int q = 0;
+  for (; q + U <= L; q += U) {
+    float xh[U][NV][8], xg[U][NV][8], a[U], s[U];
+#pragma unroll
+    for (int z = 0; z < U; ++z) {
+      const int p = pair_sorted[o + q + z];
+      const int t = p / k;
+      a[z] = act[p];
+      s[z] = ds[p];
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int col = (tid + v * nthr) * 8;
+        if (col < d) {
+          Vec8<T>::load(dOut + (size_t)t * d + col, xg[z][v]);
+          Vec8<T>::load(h + (size_t)t * d + col, xh[z][v]);
+        }
+      }
+    }
+#pragma unroll
+    for (int z = 0; z < U; ++z)
+#pragma unroll
+      for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          aV[v][c] = fmaf(a[z], xg[z][v][c], aV[v][c]);
+          aK[v][c] = fmaf(s[z], xh[z][v][c], aK[v][c]);
+        }
+  }
+  for (; q < L; ++q) {
+    const int p = pair_sorted[o + q];
+    const int t = p / k;
+    const float a = act[p], s = ds[p];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int col = (tid + v * nthr) * 8;
+      if (col < d) {
+        float xg[8], xh[8];
+        Vec8<T>::load(dOut + (size_t)t * d + col, xg);
+        Vec8<T>::load(h + (size_t)t * d + col, xh);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          aV[v][c] = fmaf(a, xg[c], aV[v][c]);
+          aK[v][c] = fmaf(s, xh[c], aK[v][c]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int col = (tid + v * nthr) * 8;
+    if (col < d) {
+      Vec8<T>::store(dV + (size_t)j * d + col, aV[v]);
+      Vec8<T>::store(dK + (size_t)j * d + col, aK[v]);
+    }
+  }
+}
+
+}  // namespace meft

@@ -1,0 +1,198 @@
+// Selection kernels: top-e blocks per token from router scores, dispatch of (token, block)
+// entries to per-block groups, and top-k neurons per token from the candidate scores.
+// Ties go to the lower index in both selections; +0 and -0 tie.
+#pragma once
+#include "common.h"
+
+namespace meft {
+
+// ---------------------------------------------------------------------------------------------
+// Top-e blocks (Algorithm 1: tau <- TopK(p, number of experts)).  One wave per token.  The row of
+// B scores sits in LDS as ordered keys; e rounds of a wave-wide arg-max, the winner is retired
+// by zeroing its key (a live key is never 0 for finite scores).  Output order: score descending,
+// block id ascending.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void route_topk_kernel(const float* __restrict__ p,
+                                                        const float* __restrict__ bias, int B, int e,
+                                                        int32_t* __restrict__ block_idx,
+                                                        float* __restrict__ block_score) {
+  extern __shared__ uint32_t s_key[];
+  const int t = blockIdx.x, lane = threadIdx.x;
+  const float* row = p + (size_t)t * B;
+  for (int b = lane; b < B; b += kWave) {
+    float v = row[b];
+    if (bias) v += bias[b];
+    s_key[b] = order_key(v);
+  }
+  __syncthreads();
+  for (int q = 0; q < e; ++q) {
+    unsigned long long best = 0ull;
+    for (int b = lane; b < B; b += kWave) {
+      const uint32_t k = s_key[b];
+      const unsigned long long c = ((unsigned long long)k << 32) | (uint32_t)(0x7FFFFFFF - b);
+      if (k != 0u && c > best) best = c;
+    }
+    best = wave_max_u64(best);
+    const int bsel = 0x7FFFFFFF - (int)(uint32_t)(best & 0xFFFFFFFFull);
+    if (lane == 0) {
+      block_idx[(size_t)t * e + q] = bsel;
+      if (block_score) block_score[(size_t)t * e + q] = key_to_float((uint32_t)(best >> 32));
+      s_key[bsel] = 0u;
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dispatch.  (1) per token, the e block ids sorted ascending (so that the concatenated candidate
+// order of a token is its ascending neuron-id order); ids are clamped into [0, B).
+// ---------------------------------------------------------------------------------------------
+__global__ void sort_blocks_kernel(const int32_t* __restrict__ block_idx, int T, int e, int B,
+                                   int32_t* __restrict__ sblk) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const int32_t* src = block_idx + (size_t)t * e;
+  int32_t* dst = sblk + (size_t)t * e;
+  for (int i = 0; i < e; ++i) {  // insertion sort; e is small
+    const int v = clampi(src[i], 0, B - 1);
+    int z = i - 1;
+    while (z >= 0 && dst[z] > v) { dst[z + 1] = dst[z]; --z; }
+    dst[z + 1] = v;
+  }
+}
+
+// exclusive scan of one int per thread over a 256-thread workgroup; returns the total in `total`
+__device__ __forceinline__ int block_excl_scan_256(int v, int* s_wave /*[4]*/, int& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int incl = wave_incl_scan(v);
+  if (lane == 63) s_wave[w] = incl;
+  __syncthreads();
+  int base = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) base += (i < w) ? s_wave[i] : 0;
+  total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+  __syncthreads();
+  return base + incl - v;
+}
+
+// (2) cnt[b] = number of entries of block b.  One workgroup per block.
+__global__ __launch_bounds__(256) void count_blocks_kernel(const int32_t* __restrict__ sblk, int n_ent,
+                                                           int32_t* __restrict__ cnt) {
+  __shared__ int s_w[4];
+  const int b = blockIdx.x;
+  int c = 0;
+  for (int i = threadIdx.x; i < n_ent; i += 256) c += (sblk[i] == b);
+  c = wave_sum_i(c);
+  if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) cnt[b] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+// (3) group_off / tile_off (prefix sums over blocks of cnt and of ceil(cnt/BM)) and the stable
+// fill perm[group_off[b] + rank] = entry, entries of a block in ascending entry order.
+__global__ __launch_bounds__(256) void fill_groups_kernel(const int32_t* __restrict__ sblk, int n_ent,
+                                                          const int32_t* __restrict__ cnt, int B, int BM,
+                                                          int32_t* __restrict__ group_off,
+                                                          int32_t* __restrict__ tile_off,
+                                                          int32_t* __restrict__ perm) {
+  __shared__ int s_w[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  int go = 0, to = 0;
+  for (int i = tid; i < b; i += 256) { const int c = cnt[i]; go += c; to += (c + BM - 1) / BM; }
+  int tot_g, tot_t;
+  block_excl_scan_256(go, s_w, tot_g);
+  block_excl_scan_256(to, s_w, tot_t);
+  if (tid == 0) {
+    group_off[b] = tot_g;
+    tile_off[b] = tot_t;
+    if (b == B - 1) {
+      group_off[B] = tot_g + cnt[b];
+      tile_off[B] = tot_t + (cnt[b] + BM - 1) / BM;
+    }
+  }
+  const int chunk = (n_ent + 255) / 256;
+  const int i0 = tid * chunk, i1 = min(n_ent, i0 + chunk);
+  int c = 0;
+  for (int i = i0; i < i1; ++i) c += (sblk[i] == b);
+  int tot;
+  int rank = block_excl_scan_256(c, s_w, tot);
+  for (int i = i0; i < i1; ++i)
+    if (sblk[i] == b) perm[tot_g + rank++] = i;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Top-k neurons of one token (Eq. 1 applied to the candidates of the chosen blocks).  One
+// workgroup per token.  The C candidate scores (fp32, candidate position = ascending neuron id)
+// are turned into ordered 32-bit keys in LDS; a most-significant-digit radix select (4 passes of
+// 8 bits) finds the key of the k-th largest and how many of its equals still belong; then one
+// ordered sweep emits the selected positions in ascending order: all keys above the threshold,
+// and the first `need` positions that equal it.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void topk_select_kernel(const float* __restrict__ sc,
+                                                          const int32_t* __restrict__ sblk, int C, int bs,
+                                                          int e, int k, int32_t* __restrict__ idx,
+                                                          float* __restrict__ act) {
+  extern __shared__ uint32_t s_keys[];  // [C]
+  __shared__ int s_hist[256];
+  __shared__ int s_w[4];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const float* row = sc + (size_t)t * C;
+  for (int i = tid; i < C; i += 256) s_keys[i] = order_key(row[i]);
+  if (tid == 0) { s_prefix = 0u; s_need = k; }
+  __syncthreads();
+
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    s_hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    for (int i = tid; i < C; i += 256) {
+      const uint32_t key = s_keys[i];
+      if ((key & himask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    // thread `tid` owns digit 255 - tid, so that an exclusive scan counts the larger digits
+    const int digit = 255 - tid;
+    const int h = s_hist[digit];
+    int tot;
+    const int above = block_excl_scan_256(h, s_w, tot);
+    const int need = s_need;
+    __syncthreads();
+    if (above < need && need <= above + h) {
+      s_prefix = prefix | ((uint32_t)digit << shift);
+      s_need = need - above;
+    }
+    __syncthreads();
+  }
+  const uint32_t thr = s_prefix;
+  const int need = s_need;  // how many keys equal to thr are selected (>= 1)
+
+  const int chunk = (C + 255) / 256;
+  const int i0 = tid * chunk, i1 = min(C, i0 + chunk);
+  int ngt = 0, neq = 0;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t key = s_keys[i];
+    ngt += key > thr;
+    neq += key == thr;
+  }
+  int tot;
+  const int packed = block_excl_scan_256(ngt | (neq << 16), s_w, tot);  // C <= 16384 < 2^15
+  int gt_before = packed & 0xFFFF, eq_before = packed >> 16;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t key = s_keys[i];
+    const bool gt = key > thr, eq = key == thr;
+    if (gt || (eq && eq_before < need)) {
+      const int slot = gt_before + min(eq_before, need);  // selected positions before this one
+      const int q = i / bs, r = i - q * bs;
+      const float v = key_to_float(key);
+      idx[(size_t)t * k + slot] = sblk[(size_t)t * e + q] * bs + r;
+      act[(size_t)t * k + slot] = v > 0.f ? v : 0.f;
+    }
+    gt_before += gt;
+    eq_before += eq;
+  }
+}
+
+}  // namespace meft

@@ -1,0 +1,137 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle (pytest -m gpu)."""
+import numpy as np
+import pytest
+
+from paper_2406_04984_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from tests import parity
+    return parity
+
+
+def _case(P, **kw):
+    cfg = synth.small_case(**kw)
+    rep = P.run_and_compare(cfg)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+    return rep
+
+
+def test_config_tiny_f32(P):
+    rep = P.run_and_compare(synth.CONFIGS["tiny_f32"])
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+    assert rep.idx_band_tokens == 0 and rep.block_band_tokens == 0
+
+
+def test_config_small_bf16(P):
+    rep = P.run_and_compare(synth.CONFIGS["small_bf16"])
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_shapes(P, dtype):
+    # token count, block size, hidden size and candidate count all off the tile sizes
+    _case(P, T=77, d=72, n_blocks=5, block_size=40, top_e=3, top_k=17, dtype=dtype, seed=101)
+    _case(P, T=300, d=200, n_blocks=7, block_size=150, top_e=2, top_k=33, dtype=dtype, seed=102)
+    _case(P, T=130, d=2056, n_blocks=3, block_size=24, top_e=2, top_k=9, dtype=dtype, seed=103)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_selections(P, dtype):
+    _case(P, T=33, d=64, n_blocks=4, block_size=16, top_e=4, top_k=64, dtype=dtype, seed=201)   # dense adapter
+    _case(P, T=33, d=64, n_blocks=1, block_size=96, top_e=1, top_k=10, dtype=dtype, seed=202)   # one expert
+    _case(P, T=33, d=64, n_blocks=6, block_size=16, top_e=2, top_k=32, dtype=dtype, seed=203)   # k = C
+    _case(P, T=33, d=64, n_blocks=6, block_size=16, top_e=1, top_k=1, dtype=dtype, seed=204)    # one neuron
+    _case(P, T=1, d=64, n_blocks=6, block_size=16, top_e=2, top_k=5, dtype=dtype, seed=205)     # one token
+    _case(P, T=40, d=8, n_blocks=48, block_size=1, top_e=6, top_k=6, dtype=dtype, seed=206)     # one neuron per expert
+
+
+def test_dense_case_matches_numpy_dense_adapter(P):
+    """top_e = n_blocks, top_k = N: the GPU result is the dense parallel adapter (Section 2)."""
+    from oracle import dense_ref
+    cfg = synth.small_case(T=50, d=64, n_blocks=4, block_size=32, top_e=4, top_k=128, dtype="f32", seed=301)
+    t = synth.make_inputs(cfg)
+    g = P.run_gpu(t)
+    dh, dK, dV = dense_ref.dense_adapter_grads(t.h, t.K, t.V, t.dOut)
+    assert P.rel_l2(g["out"], dense_ref.dense_adapter(t.h, t.K, t.V)) < 1e-4
+    assert P.rel_l2(g["dh"], dh) < 1e-4 and P.rel_l2(g["dK"], dK) < 1e-4 and P.rel_l2(g["dV"], dV) < 1e-4
+
+
+def test_empty_batch(P):
+    import torch
+    from paper_2406_04984_amd import binding as B
+    s = B.make_shape(0, 64, 4, 16, 2, 8, "bf16")
+    ws = torch.empty((B.meft_workspace_bytes(s),), dtype=torch.uint8, device="cuda")
+    z = torch.zeros((16,), dtype=torch.int32, device="cuda")
+    w = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    nt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.meft_route(s, w, w, None, z, None, ws)
+    B.meft_sparse_fwd(s, w, w, w, z, w, z, z.float(), ws)
+    B.meft_sparse_bwd(s, w, w, w, z, z.float(), w, None, w, w, z, nt, ws)
+    torch.cuda.synchronize()
+    assert int(nt.item()) == 0
+
+
+def test_exact_ties_go_to_the_lower_index(P):
+    """Duplicated router rows and duplicated keys give exactly equal scores on both sides."""
+    cfg = synth.small_case(T=64, d=64, n_blocks=8, block_size=32, top_e=3, top_k=20, dtype="bf16", seed=401)
+    t = synth.make_inputs(cfg)
+    t.Wg[5] = t.Wg[2]
+    t.Wg[7] = t.Wg[2]
+    t.K[1::2] = t.K[0::2]          # every odd neuron duplicates its even neighbour
+    t.K[40:48] = 0.0               # a run of exact zeros (+0 and -0 both appear through the products)
+    from oracle import oracle
+    g = P.run_gpu(t)
+    r = oracle.route(t.h, t.Wg, cfg.top_e, t.bias)
+    f = oracle.forward(t.h, t.K, t.V, r.block_idx, cfg.block_size, cfg.top_k, want_candidates=True)
+    b = oracle.backward(t.h, t.K, t.V, f.idx, f.score, t.dOut, cfg.block_size)
+    rep = P.compare(t, g, r, f, b)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+    # equal scores are exactly equal in both precisions here, so no tie band is needed
+    assert (np.sort(g["block_idx"], 1) == np.sort(r.block_idx, 1)).all()
+    assert (g["idx"] == np.sort(f.idx, 1)).all()
+
+
+def test_backward_accepts_any_order_inside_a_token_and_is_deterministic(P):
+    import torch
+    cfg = synth.small_case(T=200, d=128, n_blocks=8, block_size=64, top_e=2, top_k=24, dtype="bf16", seed=501)
+    t = synth.make_inputs(cfg)
+    L = P.DeviceLayer(t)
+    L.fill_grad_sentinel()
+    L.step()
+    a = L.results()
+    rng = np.random.default_rng(5)
+    perm = np.stack([rng.permutation(cfg.top_k) for _ in range(cfg.T)])
+    pt = torch.from_numpy(perm).cuda()
+    L.idx.copy_(torch.gather(L.idx, 1, pt))
+    L.act.copy_(torch.gather(L.act, 1, pt))
+    L.fill_grad_sentinel()
+    L.bwd()
+    b = L.results()
+    # dK, dV sum pairs in token order whatever the order inside a token: bit-identical
+    assert (a["dK_bits"] == b["dK_bits"]).all() and (a["dV_bits"] == b["dV_bits"]).all()
+    assert (a["touched"] == b["touched"]).all()
+    assert P.rel_l2(b["dh"], a["dh"]) < 2e-2
+    # same inputs again: every output bit-identical
+    L.fill_grad_sentinel()
+    L.bwd()
+    c = L.results()
+    for n in ("dK_bits", "dV_bits", "dh", "touched"):
+        assert (b[n] == c[n]).all(), n
+
+
+def test_two_full_runs_are_bit_identical(P):
+    cfg = synth.small_case(T=257, d=256, n_blocks=8, block_size=128, top_e=3, top_k=40, dtype="bf16", seed=601)
+    t = synth.make_inputs(cfg)
+    a, b = P.run_gpu(t), P.run_gpu(t)
+    for n in ("block_idx", "block_score", "idx", "act", "out", "dh", "dK_bits", "dV_bits", "touched"):
+        assert (a[n] == b[n]).all(), n
