@@ -144,6 +144,14 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
 void meft_profile_enable(int on);
 int meft_profile_read(const char** names, int32_t* launches, float* total_ms, int cap);
 
+/*
+ * Measurement aid (not part of the paper's method): a plain streaming copy of `bytes` bytes
+ * (a multiple of 16; both pointers 16-byte aligned device memory) as one kernel on `stream`.
+ * Gives the copy bandwidth of the machine and a dispatch of known traffic against which hardware
+ * byte counters can be scaled.  It appears in meft_profile_read as "probe_copy".
+ */
+meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,8 @@ MEFT_F32, MEFT_BF16 = 0, 1
 MEFT_FLAG_HOST_KV = 1
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
-           "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read")
+           "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
+           "meft_probe_copy")
 
 
 class MeftShape(ctypes.Structure):
@@ -53,6 +54,8 @@ _lib.meft_sparse_fwd.restype = ctypes.c_int
 _lib.meft_sparse_fwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_sparse_bwd.restype = ctypes.c_int
 _lib.meft_sparse_bwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.meft_probe_copy.restype = ctypes.c_int
+_lib.meft_probe_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.meft_profile_enable.restype = None
 _lib.meft_profile_enable.argtypes = [ctypes.c_int]
 _lib.meft_profile_read.restype = ctypes.c_int
@@ -125,6 +128,13 @@ def meft_sparse_bwd(shape, h, K, V, idx, act, dOut, dh, dK, dV, touched, n_touch
                               _p(dK), _p(dV), _p(touched), _p(n_touched), wp, wb, _stream(stream))
     if check and rc:
         raise MeftError("meft_sparse_bwd", rc)
+    return rc
+
+
+def meft_probe_copy(dst, src, nbytes: int, stream=None, check=True) -> int:
+    rc = _lib.meft_probe_copy(_p(dst), _p(src), nbytes, _stream(stream))
+    if check and rc:
+        raise MeftError("meft_probe_copy", rc)
     return rc
 
 

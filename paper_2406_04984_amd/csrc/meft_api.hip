@@ -322,6 +322,15 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   return launch_status();
 }
 
+meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0) return MEFT_ERR_INVALID_ARG;
+  if (bytes == 0) return MEFT_OK;
+  const size_t n = bytes / 16;
+  MEFT_LAUNCH("probe_copy", probe_copy_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+              static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n);
+  return launch_status();
+}
+
 void meft_profile_enable(int on) {
   for (auto& e : g_prof) {
     (void)hipEventDestroy(e.start);

@@ -13,6 +13,13 @@ __global__ void fill_i32_kernel(int32_t* __restrict__ p, size_t n, int32_t v) {
   if (i < n) p[i] = v;
 }
 
+// plain streaming copy of n 16-byte words (grid-stride); calibrates bandwidth counters
+__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                         size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
 // cnt[j] += 1 for every pair
 __global__ void pair_count_kernel(const int32_t* __restrict__ idx, int P, int N, int32_t* __restrict__ cnt) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
