@@ -1,0 +1,312 @@
+// The block-dense formulation of the layer for bf16: because every token's selected neurons lie
+// in its top_e blocks, each stage is a contraction between the tokens routed to a block and that
+// block's rows, with the activations of unselected (token, neuron) pairs set to zero.  With
+// top_k / (top_e * block_size) around 1/16 the matrix cores do this faster than per-pair row
+// gathers can move their bytes, and every operand panel is read from HBM once.
+//
+// Per block b with its token group G_b (slots, ascending token order), block_size neurons, hidden d:
+//   scores   S [G_b, bs] = h[G_b, :] . K_b^T                     (Eq. 6)            KC GEMM
+//   forward  part[G_b, d] = A'[G_b, bs] . V_b                    (Eq. 4, one block) NC GEMM
+//            out[t, :] = sum over the token's blocks of part      (row reduce)
+//   backward G [G_b, bs] = dOut[G_b, :] . V_b^T, DS' = G * [A' > 0]                 KC GEMM
+//            dhpart[G_b, d] = DS'[G_b, bs] . K_b ; dh = row reduce                 NC GEMM
+//            dV_b[bs, d] = A'^T[bs, G_b] . dOut[G_b, :]                            NC GEMM
+//            dK_b[bs, d] = DS'^T[bs, G_b] . h[G_b, :]                              NC GEMM
+// A'[slot, r] = bf16(act) where neuron r of the block is selected by the slot's token, else 0.
+#pragma once
+#include "gemm_mfma.h"
+
+namespace meft {
+
+__device__ __forceinline__ int round_up64(int v) { return (v + 63) & ~63; }
+
+// ---- problem policies for gemm_mfma_kernel ----------------------------------------------------
+
+// Router scores (Eq. 5): p[T, n_blocks] = h . Wg^T, one group.
+struct ProbRouter {
+  static constexpr bool kBNC = false;
+  const uint16_t* h; const uint16_t* Wg; float* p;
+  int T, d, B;
+  __device__ bool locate(int wg, TileCoord& tc) const {
+    const int tn = (B + kTN - 1) / kTN, mt = wg / tn;
+    tc.g = 0; tc.m0 = mt * kTM; tc.n0 = (wg - mt * tn) * kTN; tc.Mrows = T; tc.Ncols = B; tc.nk = d / kTK; tc.slot0 = 0;
+    return tc.m0 < T;
+  }
+  __device__ const uint16_t* a_row(const TileCoord&, int m) const { return h + (size_t)(m < T ? m : T - 1) * d; }
+  __device__ const uint16_t* b_row(const TileCoord&, int n) const { return Wg + (size_t)(n < B ? n : B - 1) * d; }
+  __device__ void store4(const TileCoord&, int m, int n, const float (&v)[4]) const {
+    if (n >= B) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (m + i < T) p[(size_t)(m + i) * B + n] = v[i];
+  }
+};
+
+// Token-major, B contiguous along k: rows = tokens of the group (gathered through perm), columns =
+// the block's neurons.  MASKED = false: key scores, written fp32 by entry.  MASKED = true: the
+// activation gradient, masked by A' > 0, written bf16 both slot-major (DS') and neuron-major (DS'^T).
+template <bool MASKED>
+struct ProbTokKC {
+  static constexpr bool kBNC = false;
+  const uint16_t* X;          // h (scores) or dOut (activation gradient), [T, d]
+  const uint16_t* W;          // K or V, [N, d]
+  const int32_t* perm; const int32_t* group_off; const int32_t* goffp;
+  TokenSched sched;
+  int e, bs, bsp, d;
+  float* sc;                  // !MASKED: [T*e, bs]
+  const uint16_t* Ap;         // MASKED: A' [slots, bsp]
+  uint16_t* DS; uint16_t* DST;
+  __device__ bool locate(int wg, TileCoord& tc) const {
+    int mt, nt, rows;
+    if (!locate_token_tile(sched, group_off, wg, (bs + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
+    tc.m0 = mt * kTM; tc.n0 = nt * kTN; tc.Mrows = rows; tc.Ncols = bs; tc.nk = d / kTK;
+    return true;
+  }
+  __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
+    const int ent = perm[tc.slot0 + (m < tc.Mrows ? m : tc.Mrows - 1)];
+    return X + (size_t)(ent / e) * d;
+  }
+  __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
+    return W + ((size_t)tc.g * bs + (n < bs ? n : bs - 1)) * d;
+  }
+  __device__ void store4(const TileCoord& tc, int m, int n, const float (&v)[4]) const {
+    if constexpr (!MASKED) {
+      if (n >= bs) return;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (m + i < tc.Mrows) sc[(size_t)perm[tc.slot0 + m + i] * bs + n] = v[i];
+    } else {
+      const int Mgp = round_up64(tc.Mrows);
+      uint32_t b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool in = (m + i < tc.Mrows) && (n < bs);
+        const size_t at = (size_t)(tc.slot0 + (in ? m + i : 0)) * bsp + (in ? n : 0);
+        const bool on = in && (Ap[at] & 0x7FFFu) != 0 && !(Ap[at] & 0x8000u);
+        b[i] = on ? f32_to_bf16_bits(v[i]) : 0u;
+        if (m + i < tc.Mrows && n < bsp) DS[(size_t)(tc.slot0 + m + i) * bsp + n] = (uint16_t)b[i];
+      }
+      if (n < bs && m < Mgp) {
+        uint2 w = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
+        *reinterpret_cast<uint2*>(DST + ((size_t)goffp[tc.g] * bs + (size_t)n * Mgp + m)) = w;
+      }
+    }
+  }
+};
+
+// Token-major, B contiguous along n: part[slot, :] = A[slot, 0:bs] . W_b   (W = V: forward value sum;
+// W = K: dh).  A is slot-major [slots, bsp] with zero padding in columns bs..bsp.
+struct ProbTokNC {
+  static constexpr bool kBNC = true;
+  const uint16_t* A;          // A' or DS'
+  const uint16_t* W;          // V or K, [N, d]
+  const int32_t* group_off;
+  TokenSched sched;
+  int bs, bsp, d;
+  float* part;                // [slots, d]
+  __device__ bool locate(int wg, TileCoord& tc) const {
+    int mt, nt, rows;
+    if (!locate_token_tile(sched, group_off, wg, (d + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
+    tc.m0 = mt * kTM; tc.n0 = nt * kTN; tc.Mrows = rows; tc.Ncols = d; tc.nk = bsp / kTK;
+    return true;
+  }
+  __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
+    return A + (size_t)(tc.slot0 + (m < tc.Mrows ? m : tc.Mrows - 1)) * bsp;
+  }
+  __device__ const uint16_t* b_row(const TileCoord& tc, int k) const {
+    return W + ((size_t)tc.g * bs + (k < bs ? k : bs - 1)) * d;
+  }
+  __device__ void store4(const TileCoord& tc, int m, int n, const float (&v)[4]) const {
+    if (n >= d) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (m + i < tc.Mrows) part[(size_t)(tc.slot0 + m + i) * d + n] = v[i];
+  }
+};
+
+// Neuron-major, B contiguous along n: G_b[bs, d] = AT_b[bs, slots] . X[token(slot), :]
+// (AT = A'^T, X = dOut: dV;  AT = DS'^T, X = h: dK).  Only rows whose neuron is touched are written.
+struct ProbNeuNC {
+  static constexpr bool kBNC = true;
+  const uint16_t* AT;         // per group [bs, Mgp] at element offset goffp[g]*bs
+  const uint16_t* X;          // [T, d]
+  const int32_t* group_off; const int32_t* goffp; const int32_t* tok_of_slot;
+  const int32_t* flag;        // [N] > 0 where some token selected the neuron
+  int n_groups, bs, d;
+  uint16_t* G;                // dV or dK [N, d]
+  __device__ bool locate(int wg, TileCoord& tc) const {
+    const int tm = (bs + kTM - 1) / kTM, tn = (d + kTN - 1) / kTN;
+    const int x = wg & (kXcd - 1), local = wg >> 3;
+    const int gi = local / (tm * tn), w = local - gi * (tm * tn);
+    tc.g = x + kXcd * gi;
+    if (tc.g >= n_groups) return false;
+    tc.slot0 = group_off[tc.g];
+    const int rows = group_off[tc.g + 1] - tc.slot0;
+    if (rows == 0) return false;
+    tc.m0 = (w / tn) * kTM; tc.n0 = (w % tn) * kTN; tc.Mrows = bs; tc.Ncols = d; tc.nk = round_up64(rows) / kTK;
+    tc.aux = rows;
+    return true;
+  }
+  __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
+    return AT + (size_t)goffp[tc.g] * bs + (size_t)(m < bs ? m : bs - 1) * round_up64(tc.aux);
+  }
+  __device__ const uint16_t* b_row(const TileCoord& tc, int k) const {
+    // k is wave-uniform here; reading through the constant address space makes this a scalar load, which
+    // is counted apart from the vector loads that pace the operand pipeline
+    const auto* tos = reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(
+        reinterpret_cast<uintptr_t>(tok_of_slot));
+    return X + (size_t)tos[tc.slot0 + (k < tc.aux ? k : tc.aux - 1)] * d;
+  }
+  __device__ void store4(const TileCoord& tc, int m, int n, const float (&v)[4]) const {
+    if (n >= d) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = m + i;
+      if (r < bs) {
+        const size_t j = (size_t)tc.g * bs + r;
+        if (flag[j] > 0) G[j * d + n] = (uint16_t)f32_to_bf16_bits(v[i]);
+      }
+    }
+  }
+};
+
+// ---- helper kernels ----------------------------------------------------------------------------
+
+// Backward: the distinct blocks of a token's selected neurons, ascending, padded with -1 to top_e
+// entries.  One wave per token; block ids go through an LDS bitmap.  More than top_e distinct blocks
+// is a caller error: the extra blocks are dropped (their pairs then contribute nothing).
+__global__ __launch_bounds__(64) void blocks_from_idx_kernel(const int32_t* __restrict__ idx, int k, int N, int bs,
+                                                             int n_blocks, int e, int32_t* __restrict__ sblk) {
+  extern __shared__ uint32_t s_bits[];  // [ceil(n_blocks/32)]
+  const int t = blockIdx.x, lane = threadIdx.x;
+  const int words = (n_blocks + 31) / 32;
+  for (int w = lane; w < words; w += 64) s_bits[w] = 0u;
+  __syncthreads();
+  for (int i = lane; i < k; i += 64) {
+    const int b = clampi(idx[(size_t)t * k + i], 0, N - 1) / bs;
+    atomicOr(&s_bits[b >> 5], 1u << (b & 31));
+  }
+  __syncthreads();
+  int base = 0;
+  for (int w0 = 0; w0 < words; w0 += 64) {
+    const int w = w0 + lane;
+    uint32_t bits = w < words ? s_bits[w] : 0u;
+    const int c = __popc(bits);
+    const int incl = wave_incl_scan(c);
+    int pos = base + incl - c;
+    while (bits) {
+      const int b = __ffs(bits) - 1;
+      bits &= bits - 1;
+      if (pos < e) sblk[(size_t)t * e + pos] = w * 32 + b;
+      ++pos;
+    }
+    base += __shfl(incl, 63, 64);
+  }
+  for (int q = base + lane; q < e; q += 64) sblk[(size_t)t * e + q] = -1;
+}
+
+// After fill_groups: slot -> token, entry -> slot, and the prefix of 64-padded group sizes.
+__global__ __launch_bounds__(256) void slot_maps_kernel(const int32_t* __restrict__ perm,
+                                                        const int32_t* __restrict__ group_off, int n_groups, int e,
+                                                        int32_t* __restrict__ tok_of_slot,
+                                                        int32_t* __restrict__ slot_of_ent,
+                                                        int32_t* __restrict__ goffp) {
+  const int n_slots = group_off[n_groups];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_slots) {
+    const int ent = perm[i];
+    tok_of_slot[i] = ent / e;
+    slot_of_ent[ent] = i;
+  }
+  if (blockIdx.x == 0) {
+    // serial prefix over groups by one thread per 256-group chunk would need a scan; n_groups is small
+    if (threadIdx.x == 0) {
+      int acc = 0;
+      for (int g = 0; g < n_groups; ++g) {
+        goffp[g] = acc;
+        acc += round_up64(group_off[g + 1] - group_off[g]);
+      }
+      goffp[n_groups] = acc;
+    }
+  }
+}
+
+// Backward: scatter the saved activations into A' (slot-major) and A'^T (neuron-major), and mark
+// touched neurons.  Both buffers must be zero before.  One thread per (token, neuron) pair.
+__global__ void scatter_act_kernel(const int32_t* __restrict__ idx, const float* __restrict__ act, int P, int k,
+                                   int N, int bs, int bsp, int e, const int32_t* __restrict__ sblk,
+                                   const int32_t* __restrict__ slot_of_ent, const int32_t* __restrict__ group_off,
+                                   const int32_t* __restrict__ goffp, uint16_t* __restrict__ Ap,
+                                   uint16_t* __restrict__ ApT, int32_t* __restrict__ flag) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= P) return;
+  const int t = p / k;
+  const int j = clampi(idx[p], 0, N - 1);
+  const int b = j / bs, r = j - b * bs;
+  flag[j] = 1;
+  int q = -1;
+  for (int z = 0; z < e; ++z)
+    if (sblk[(size_t)t * e + z] == b) { q = z; break; }
+  if (q < 0) return;
+  const int slot = slot_of_ent[t * e + q];
+  const uint16_t v = (uint16_t)f32_to_bf16_bits(act[p]);
+  Ap[(size_t)slot * bsp + r] = v;
+  const int s0 = group_off[b], Mgp = round_up64(group_off[b + 1] - s0);
+  ApT[(size_t)goffp[b] * bs + (size_t)r * Mgp + (slot - s0)] = v;
+}
+
+// out[t, :] = sum over the token's entries of part[slot(entry), :], rounded once to bf16.
+template <int NV>
+__global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ part,
+                                                           const int32_t* __restrict__ sblk,
+                                                           const int32_t* __restrict__ slot_of_ent, int d, int e,
+                                                           uint16_t* __restrict__ out) {
+  const int t = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
+  float acc[NV][8];
+#pragma unroll
+  for (int v = 0; v < NV; ++v)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[v][c] = 0.f;
+  for (int q = 0; q < e; ++q) {
+    if (sblk[(size_t)t * e + q] < 0) continue;
+    const float* row = part + (size_t)slot_of_ent[t * e + q] * d;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int col = (tid + v * nthr) * 8;
+      if (col < d) {
+        float x[8];
+        Vec8<float>::load(row + col, x);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[v][c] += x[c];
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int col = (tid + v * nthr) * 8;
+    if (col < d) Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(out) + (size_t)t * d + col, acc[v]);
+  }
+}
+
+// touched = ascending ids with flag > 0 (one workgroup of 1024).
+__global__ __launch_bounds__(1024) void compact_flags_kernel(const int32_t* __restrict__ flag, int N,
+                                                             int32_t* __restrict__ touched,
+                                                             int32_t* __restrict__ n_touched) {
+  __shared__ int s_f[16];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int chunk = (N + 1023) / 1024;
+  const int j0 = min(N, tid * chunk), j1 = min(N, j0 + chunk);
+  int f = 0;
+  for (int j = j0; j < j1; ++j) f += flag[j] > 0;
+  const int fi = wave_incl_scan(f);
+  if (lane == 63) s_f[w] = fi;
+  __syncthreads();
+  int fb = 0;
+  for (int i = 0; i < w; ++i) fb += s_f[i];
+  int nt = fb + fi - f;
+  for (int j = j0; j < j1; ++j)
+    if (flag[j] > 0) touched[nt++] = j;
+  if (tid == 1023) *n_touched = nt;
+}
+
+}  // namespace meft

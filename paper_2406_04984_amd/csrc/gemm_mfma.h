@@ -1,0 +1,275 @@
+// Grouped bf16 GEMM core for gfx950 matrix cores, shared by every dense contraction of the layer:
+//
+//   C[m, n] = sum_k A[m, k] * B(k, n)          fp32 accumulation, v_mfma_f32_32x32x16_bf16
+//
+// A is always contiguous along k.  B is either contiguous along k ("KC": rows indexed by n, used for
+// the router and key scores, Eq. 5 / Eq. 6, and for dOut.V^T in the backward) or contiguous along n
+// ("NC": rows indexed by k, used where the contraction runs over neurons or tokens: the value sum of
+// Eq. 4, dh, dK, dV).
+//
+// Tile 128 (m) x 256 (n) x 64 (k), 4 waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles.
+// Operands go global -> LDS directly (global_load_lds, 16 B per lane), three stages of 48 KB in a
+// ring with one barrier per k tile; the wait for a stage is a partial vmcnt so that the next
+// stage's loads stay in flight.  LDS layouts are XOR-swizzled so that both the linear DMA writes
+// and the fragment reads are free of bank conflicts:
+//   k-contiguous operand: rows of 64 k = 8 chunks of 16 B; logical chunk c of row r sits at chunk
+//     c ^ ((r >> 1) & 7); fragments are read with ds_read_b128.
+//   n-contiguous operand: rows of 256 n = 32 chunks of 16 B; logical chunk c of row k sits at chunk
+//     c ^ (2 * (k & 7)); fragments are read with the transposing ds_read_b64_tr_b16, which hands
+//     lane i of a 16-lane group the four k-consecutive values of column i of a 4 x 16 block.
+//
+// Workgroups are mapped to tiles XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs,
+// so workgroup id w works for XCD w % 8, and all tiles of one group (block of neurons) are given to
+// one XCD, consecutively, so that the group's operand panels are fetched from HBM once and shared in
+// that XCD's L2.
+#pragma once
+#include "common.h"
+
+namespace meft {
+
+constexpr int kTM = 128, kTN = 256, kTK = 64, kStages = 3;
+constexpr int kStageElems = (kTM + kTN) * kTK;                 // 24576 bf16 = 48 KB
+constexpr int kGemmLdsBytes = kStages * kStageElems * 2;       // 144 KB
+constexpr int kXcd = 8;
+
+#define MEFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define MEFT_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+struct TileCoord {
+  int g;       // group (block of neurons); 0 for an ungrouped problem
+  int m0, n0;  // first row / column of the tile inside the group's problem
+  int Mrows;   // rows of the group's problem
+  int Ncols;   // columns of the group's problem
+  int nk;      // k tiles
+  int slot0;   // first slot of the group in the slot-ordered arrays (token-grouped problems)
+  int aux;     // policy-defined
+};
+
+// A problem policy P provides:
+//   static constexpr bool kBNC;                         B contiguous along n?
+//   __device__ bool locate(int wg, TileCoord&) const;   false: no tile for this workgroup
+//   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
+//   __device__ const uint16_t* b_row(const TileCoord&, int r) const;   KC: row n; NC: row k (clamped)
+//   __device__ void store4(const TileCoord&, int m, int n, const float (&v)[4]) const;  rows m..m+3 of column n
+//
+// Epilogue contract: acc[i][j][r] of a wave holds C[m][n] with
+//   m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,   n = wn + j*32 + lane%32   (tile-local).
+// store4 receives, per (i, j, r/4), four consecutive rows of one column.
+
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Eight transposing LDS reads (the four n-contiguous B fragments of one k16 step, low and high k half)
+// followed by the wait for them.  Written as one asm block: issued through the builtin, the compiler
+// would order these reads after every outstanding global->LDS load (it cannot tell the stages apart),
+// which would drain the operand pipeline at every k tile.  The barrier that hands a stage over already
+// guarantees that the stage read here has landed.
+template <int OFF>
+__device__ __forceinline__ void tr_read8(u32x2 (&o)[8], const uint32_t (&alo)[4], const uint32_t (&ahi)[4]) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %8 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %1, %9 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %2, %10 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %3, %11 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %4, %12 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %6, %14 offset:%16\n\t"
+      "ds_read_b64_tr_b16 %7, %15 offset:%16\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]), "=&v"(o[6]), "=&v"(o[7])
+      : "v"(alo[0]), "v"(ahi[0]), "v"(alo[1]), "v"(ahi[1]), "v"(alo[2]), "v"(ahi[2]), "v"(alo[3]), "v"(ahi[3]),
+        "n"(OFF)
+      : "memory");
+}
+
+template <class P>
+__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  TileCoord tc;
+  if (!p.locate(blockIdx.x, tc)) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int LA = kTM / 8 / 4;                    // A wave-loads (8 rows x 128 B) per wave and stage: 4
+  constexpr int LB = 8;                              // B wave-loads per wave and stage (KC: 8 rows x 128 B; NC: 2 rows x 512 B)
+
+  // ---- global -> LDS addressing ----
+  const int lr8 = lane >> 3;
+  const uint16_t* pa[LA];
+#pragma unroll
+  for (int i = 0; i < LA; ++i) {
+    const int row = (wave * LA + i) * 8 + lr8;
+    pa[i] = p.a_row(tc, tc.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+  }
+  const uint16_t* pb[LB];  // KC: fixed row pointers, advanced by k.  NC: recomputed per k tile.
+  int nc_col = 0;          // NC: element offset of this lane's chunk inside a B row (without swizzle)
+  if constexpr (!P::kBNC) {
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int row = (wave * LB + i) * 8 + lr8;
+      pb[i] = p.b_row(tc, tc.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+    }
+  } else {
+    nc_col = tc.n0;
+  }
+  auto issue = [&](int kt, int stage) {
+    uint16_t* sa = smem + stage * kStageElems;
+    uint16_t* sb = sa + kTM * kTK;
+#pragma unroll
+    for (int i = 0; i < LA; ++i)
+      __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + kt * kTK), MEFT_LPTR(sa + (wave * LA + i) * 8 * kTK), 16, 0, 0);
+    if constexpr (!P::kBNC) {
+#pragma unroll
+      for (int i = 0; i < LB; ++i)
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(pb[i] + kt * kTK), MEFT_LPTR(sb + (wave * LB + i) * 8 * kTK), 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < LB; ++i) {
+        const int kev = 2 * (wave * LB + i);                          // even k row of this wave-load (wave-uniform)
+        const int krow = kev + (lane >> 5);                           // this lane's k row inside the tile
+        const int chunk = (lane & 31) ^ (2 * (krow & 7));             // logical 16-byte chunk this lane fetches
+        int col = nc_col + chunk * 8;
+        col = col > tc.Ncols - 8 ? tc.Ncols - 8 : col;                // clamp (columns beyond Ncols are never stored)
+        // both row pointers are wave-uniform, so any index look-up behind them is a scalar load and
+        // does not disturb the vector-memory counter that paces the pipeline
+        const uint16_t* r0 = p.b_row(tc, kt * kTK + kev);
+        const uint16_t* r1 = p.b_row(tc, kt * kTK + kev + 1);
+        const uint16_t* src = ((lane >> 5) ? r1 : r0) + col;
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (wave * LB + i) * 512), 16, 0, 0);
+      }
+    }
+  };
+
+  // ---- fragment addressing ----
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+  const int fr = lane & 31, fc = lane >> 5;
+  int offA[2], keyA[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) { const int r = wm + i * 32 + fr; offA[i] = r * kTK; keyA[i] = (r >> 1) & 7; }
+  int offB[4], keyB[4];  // KC only
+  uint32_t tr_lo[4], tr_hi[4];  // NC only: LDS byte offsets (inside a stage's B region) of this lane's transposing reads
+  if constexpr (!P::kBNC) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { const int r = wn + j * 32 + fr; offB[j] = kTM * kTK + r * kTK; keyB[j] = (r >> 1) & 7; }
+  } else {
+    // lane s of a 16-lane group points at row (k base + s/4), columns 4*(s%4)..+3 of a 4 x 16 block and
+    // receives column s of that block, four consecutive k.  Low half: k = 8*(lane/32) + 0..3, high half +4.
+    const int gq = lane >> 4, s = lane & 15;
+    const int k_lo = 8 * (gq >> 1) + (s >> 2), k_hi = k_lo + 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = wn + j * 32 + 16 * (gq & 1) + 4 * (s & 3);
+      tr_lo[j] = (uint32_t)(k_lo * 256 + (((n >> 3) ^ (2 * (k_lo & 7))) << 3) + (n & 7)) * 2u;
+      tr_hi[j] = (uint32_t)(k_hi * 256 + (((n >> 3) ^ (2 * (k_hi & 7))) << 3) + (n & 7)) * 2u;
+    }
+  }
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = tc.nk;
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s)
+    if (s < nk) issue(s, s);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    // tile kt has landed once at most the loads of one later tile are still outstanding
+    if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (kt + kStages - 1 < nk) {
+      int ps = stage - 1;
+      if (ps < 0) ps += kStages;
+      issue(kt + kStages - 1, ps);  // the buffer of tile kt-1: every wave is past it (barrier above)
+    }
+    const uint16_t* st = smem + stage * kStageElems;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 fa[2], fb[4];
+      const int c = ks * 2 + fc;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
+      if constexpr (!P::kBNC) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
+      } else {
+        // k16 step ks starts 16 rows = 8192 bytes further; that does not change (k & 7), so the swizzle holds
+        const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
+        uint32_t alo[4], ahi[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
+        u32x2 o[8];
+        if (ks == 0) tr_read8<0>(o, alo, ahi);
+        else if (ks == 1) tr_read8<8192>(o, alo, ahi);
+        else if (ks == 2) tr_read8<16384>(o, alo, ahi);
+        else tr_read8<24576>(o, alo, ahi);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
+          fb[j] = __builtin_bit_cast(bf16x8, w);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    stage = stage + 1 == kStages ? 0 : stage + 1;
+  }
+
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = tc.n0 + wn + j * 32 + fr;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int m = tc.m0 + wm + i * 32 + q * 8 + fc * 4;
+        const float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        p.store4(tc, m, n, v);  // rows m..m+3 of column n
+      }
+    }
+}
+
+// ---- tile schedule shared by the token-major problems ----------------------------------------
+// sched[x][i] = (group, m tile) pairs that XCD x works through, in order; sched_len[x] their number.
+struct TokenSched {
+  const int2* pairs;     // [kXcd][cap]
+  const int* len;        // [kXcd]
+  int cap;
+};
+
+// One thread per XCD lists the m tiles of its groups (groups g with g % 8 == x).
+__global__ void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups, int cap,
+                                   int2* __restrict__ pairs, int* __restrict__ len) {
+  const int x = threadIdx.x;
+  if (x >= kXcd) return;
+  int n = 0;
+  for (int g = x; g < n_groups; g += kXcd) {
+    const int rows = group_off[g + 1] - group_off[g];
+    const int tm = (rows + kTM - 1) / kTM;
+    for (int i = 0; i < tm && n < cap; ++i) pairs[(size_t)x * cap + n++] = make_int2(g, i);
+  }
+  len[x] = n;
+}
+
+__device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,
+                                                   int& g, int& mt, int& nt, int& slot0, int& rows) {
+  const int x = wg & (kXcd - 1), local = wg >> 3;
+  const int pi = local / tn;
+  if (pi >= s.len[x]) return false;
+  nt = local - pi * tn;
+  const int2 gm = s.pairs[(size_t)x * s.cap + pi];
+  g = gm.x;
+  mt = gm.y;
+  slot0 = group_off[g];
+  rows = group_off[g + 1] - slot0;
+  return true;
+}
+
+}  // namespace meft

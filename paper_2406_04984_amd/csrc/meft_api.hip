@@ -10,6 +10,7 @@
 
 #include "../../include/meft.h"
 #include "common.h"
+#include "dense_path.h"
 #include "gather.h"
 #include "gemm_nt.h"
 #include "scatter.h"
@@ -86,6 +87,17 @@ struct Carver {
   }
 };
 
+// The matrix-core formulation (dense_path.h) is used for bf16 when the hidden size fits its k tiling and
+// the selection is dense enough inside the chosen blocks; otherwise, and for fp32, the per-pair gather
+// kernels are used.
+bool use_dense(const meft_shape& s) {
+  const int64_t C = (int64_t)s.top_e * s.block_size;
+  return s.dtype == MEFT_BF16 && s.d % kTK == 0 && s.block_size >= 16 && (int64_t)s.top_k * 64 >= C;
+}
+
+int round64(int v) { return (v + 63) & ~63; }
+int sched_cap(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + (s.n_blocks + kXcd - 1) / kXcd + 1); }
+
 struct RouteWs {
   float* p;
   size_t bytes;
@@ -96,36 +108,77 @@ struct RouteWs {
   }
 };
 
-struct FwdWs {
-  int32_t *sblk, *cnt, *group_off, *tile_off, *perm;
-  float* sc;
-  size_t bytes;
-  FwdWs(const meft_shape& s, void* ws) {
-    Carver c(ws);
+// index structures of the (token, block) dispatch, common to forward and backward
+struct DispatchWs {
+  int32_t *sblk = nullptr, *cnt = nullptr, *group_off = nullptr, *tile_off = nullptr, *perm = nullptr,
+          *tok_of_slot = nullptr, *slot_of_ent = nullptr, *goffp = nullptr, *sched_len = nullptr;
+  int2* sched_pairs = nullptr;
+  void carve(const meft_shape& s, Carver& c) {
     const size_t n_ent = (size_t)s.T * s.top_e;
     sblk = c.take<int32_t>(n_ent);
     cnt = c.take<int32_t>(s.n_blocks);
     group_off = c.take<int32_t>((size_t)s.n_blocks + 1);
     tile_off = c.take<int32_t>((size_t)s.n_blocks + 1);
     perm = c.take<int32_t>(n_ent);
+    tok_of_slot = c.take<int32_t>(n_ent);
+    slot_of_ent = c.take<int32_t>(n_ent);
+    goffp = c.take<int32_t>((size_t)s.n_blocks + 1);
+    sched_len = c.take<int32_t>(kXcd);
+    sched_pairs = c.take<int2>((size_t)kXcd * sched_cap(s));
+  }
+};
+
+struct FwdWs : DispatchWs {
+  float* sc;
+  uint16_t* Ap;   // dense path: A' [T*e, bsp]
+  float* part;    // dense path: per-entry partial outputs [T*e, d]
+  size_t bytes;
+  FwdWs(const meft_shape& s, void* ws) {
+    Carver c(ws);
+    carve(s, c);
+    const size_t n_ent = (size_t)s.T * s.top_e;
     sc = c.take<float>(n_ent * s.block_size);
+    Ap = nullptr; part = nullptr;
+    if (use_dense(s)) {
+      Ap = c.take<uint16_t>(n_ent * round64(s.block_size));
+      part = c.take<float>(n_ent * s.d);
+    }
     bytes = c.off;
   }
 };
 
-struct BwdWs {
+struct BwdWs : DispatchWs {
+  // gather path
   float* ds;
-  int32_t *cnt, *cursor, *seg_off, *pair_list, *pair_sorted;
+  int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted;
+  // dense path
+  int32_t* flag;
+  uint16_t *Ap, *ApT, *DS, *DST;
+  float* part;
   size_t bytes;
   BwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
     const size_t P = (size_t)s.T * s.top_k;
-    ds = c.take<float>(P);
-    cnt = c.take<int32_t>(s.N);     // cnt and cursor are adjacent: cleared by one fill
-    cursor = c.take<int32_t>(s.N);
-    seg_off = c.take<int32_t>((size_t)s.N + 1);
-    pair_list = c.take<int32_t>(P);
-    pair_sorted = c.take<int32_t>(P);
+    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = flag = nullptr;
+    Ap = ApT = DS = DST = nullptr; part = nullptr;
+    if (use_dense(s)) {
+      carve(s, c);
+      const size_t n_ent = (size_t)s.T * s.top_e;
+      const size_t slots_p = n_ent + (size_t)64 * s.n_blocks;   // group sizes padded to 64
+      flag = c.take<int32_t>(s.N);
+      Ap = c.take<uint16_t>(n_ent * round64(s.block_size));      // Ap and ApT adjacent: cleared by one fill
+      ApT = c.take<uint16_t>(slots_p * s.block_size);
+      DS = c.take<uint16_t>(n_ent * round64(s.block_size));
+      DST = c.take<uint16_t>(slots_p * s.block_size);
+      part = c.take<float>(n_ent * s.d);
+    } else {
+      ds = c.take<float>(P);
+      cnt_n = c.take<int32_t>(s.N);     // cnt_n and cursor are adjacent: cleared by one fill
+      cursor = c.take<int32_t>(s.N);
+      seg_off = c.take<int32_t>((size_t)s.N + 1);
+      pair_list = c.take<int32_t>(P);
+      pair_sorted = c.take<int32_t>(P);
+    }
     bytes = c.off;
   }
 };
@@ -200,6 +253,42 @@ void launch_seg_reduce(const meft_shape& s, const BwdWs& w, const int32_t* touch
 #undef SR
 }
 
+
+template <class P>
+void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st) {
+  static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    configured = true;
+  }
+  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(grid), dim3(256), kGemmLdsBytes, st, prob);
+}
+
+// (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
+void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, hipStream_t st) {
+  const int n_ent = s.T * s.top_e;
+  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(256), 0, st, w.sblk, n_ent, w.cnt);
+  MEFT_LAUNCH("fill_groups", fill_groups_kernel, dim3(s.n_blocks), dim3(256), 0, st, w.sblk, n_ent, w.cnt,
+              s.n_blocks, BM, w.group_off, w.tile_off, w.perm);
+  if (dense) {
+    MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
+                s.n_blocks, s.top_e, w.tok_of_slot, w.slot_of_ent, w.goffp);
+    MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(64), 0, st, w.group_off, s.n_blocks,
+                sched_cap(s), w.sched_pairs, w.sched_len);
+  }
+}
+
+template <int NVDUMMY = 0>
+void launch_reduce_parts(const meft_shape& s, const float* part, const DispatchWs& w, void* out, hipStream_t st) {
+  int nthr, nv;
+  row_launch(s.d, nthr, nv);
+  uint16_t* o = static_cast<uint16_t*>(out);
+#define RP(NV) MEFT_LAUNCH("reduce_parts", (reduce_parts_kernel<NV>), dim3(s.T), dim3(nthr), 0, st, part, w.sblk, w.slot_of_ent, s.d, s.top_e, o)
+  switch (nv) { case 1: RP(1); break; case 2: RP(2); break; case 4: RP(4); break; default: RP(8); }
+#undef RP
+}
+
 }  // namespace
 }  // namespace meft
 
@@ -236,11 +325,16 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  GemmNTArgs a{};
-  a.A = h; a.Bm = Wg; a.C = w.p; a.perm = nullptr; a.group_off = nullptr; a.tile_off = nullptr;
-  a.n_groups = 1; a.M = s.T; a.Ng = s.n_blocks; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d; a.ldc = s.n_blocks;
-  a.e = 1;
-  launch_gemm_nt(s, a, (s.T + kGemmBM - 1) / kGemmBM, (s.T + kGemmF32BM - 1) / kGemmF32BM, "router_gemm", st);
+  if (s.dtype == MEFT_BF16 && s.d % kTK == 0) {
+    ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), w.p, s.T, s.d, s.n_blocks};
+    launch_gemm_mfma("router_gemm", pr, ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
+  } else {
+    GemmNTArgs a{};
+    a.A = h; a.Bm = Wg; a.C = w.p; a.perm = nullptr; a.group_off = nullptr; a.tile_off = nullptr;
+    a.n_groups = 1; a.M = s.T; a.Ng = s.n_blocks; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d; a.ldc = s.n_blocks;
+    a.e = 1;
+    launch_gemm_nt(s, a, (s.T + kGemmBM - 1) / kGemmBM, (s.T + kGemmF32BM - 1) / kGemmF32BM, "router_gemm", st);
+  }
   MEFT_LAUNCH("route_topk", route_topk_kernel, dim3(s.T), dim3(64), (size_t)s.n_blocks * 4, st, w.p, bias,
               s.n_blocks, s.top_e, block_idx, block_score);
   return launch_status();
@@ -262,24 +356,41 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   const int C = s.top_e * s.block_size;
   const int BM = s.dtype == MEFT_BF16 ? kGemmBM : kGemmF32BM;
 
+  const bool dense = use_dense(s);
   MEFT_LAUNCH("sort_blocks", sort_blocks_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, block_idx, s.T,
               s.top_e, s.n_blocks, w.sblk);
-  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(256), 0, st, w.sblk, n_ent, w.cnt);
-  MEFT_LAUNCH("fill_groups", fill_groups_kernel, dim3(s.n_blocks), dim3(256), 0, st, w.sblk, n_ent, w.cnt,
-              s.n_blocks, BM, w.group_off, w.tile_off, w.perm);
-
-  GemmNTArgs a{};
-  a.A = h; a.Bm = K; a.C = w.sc; a.perm = w.perm; a.group_off = w.group_off; a.tile_off = w.tile_off;
-  a.n_groups = s.n_blocks; a.M = 0; a.Ng = s.block_size; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d;
-  a.ldc = s.block_size; a.e = s.top_e;
-  // upper bound on the number of m-tiles: every group may end with one partial tile
-  const int nb_used = s.n_blocks < n_ent ? s.n_blocks : n_ent;
-  launch_gemm_nt(s, a, n_ent / kGemmBM + nb_used, n_ent / kGemmF32BM + nb_used, "score_gemm", st);
-
+  launch_dispatch(s, w, BM, dense, st);
+  const int bsp = round64(s.block_size);
+  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
+  const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
+                 *vv = static_cast<const uint16_t*>(V);
+  if (dense) {
+    ProbTokKC<false> ps{};
+    ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
+    ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
+    launch_gemm_mfma("score_gemm", ps, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
+  } else {
+    GemmNTArgs a{};
+    a.A = h; a.Bm = K; a.C = w.sc; a.perm = w.perm; a.group_off = w.group_off; a.tile_off = w.tile_off;
+    a.n_groups = s.n_blocks; a.M = 0; a.Ng = s.block_size; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d;
+    a.ldc = s.block_size; a.e = s.top_e;
+    // upper bound on the number of m-tiles: every group may end with one partial tile
+    const int nb_used = s.n_blocks < n_ent ? s.n_blocks : n_ent;
+    launch_gemm_nt(s, a, n_ent / kGemmBM + nb_used, n_ent / kGemmF32BM + nb_used, "score_gemm", st);
+  }
   MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
-              s.block_size, s.top_e, s.top_k, idx, act);
-  if (s.dtype == MEFT_BF16) launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
-  else launch_gather_fwd<float>(s, V, idx, act, out, st);
+              s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
+  if (dense) {
+    ProbTokNC pv{};
+    pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
+    pv.d = s.d; pv.part = w.part;
+    launch_gemm_mfma("value_gemm", pv, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
+    launch_reduce_parts(s, w.part, w, out, st);
+  } else if (s.dtype == MEFT_BF16) {
+    launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
+  } else {
+    launch_gather_fwd<float>(s, V, idx, act, out, st);
+  }
   return launch_status();
 }
 
@@ -303,14 +414,54 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   }
   const int P = s.T * s.top_k;
 
+  if (use_dense(s)) {
+    const int n_ent = s.T * s.top_e;
+    const int bsp = round64(s.block_size);
+    const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
+                   *vv = static_cast<const uint16_t*>(V), *gg = static_cast<const uint16_t*>(dOut);
+    MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
+                st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
+    launch_dispatch(s, w, kGemmBM, true, st);
+    // flag, A', A'^T start from zero (flag..ApT are adjacent in the workspace); 4-byte fill
+    const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.DS) - reinterpret_cast<char*>(w.flag)) / 4;
+    MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
+                clear_words, 0);
+    MEFT_LAUNCH("scatter_act", scatter_act_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, act, P, s.top_k,
+                s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.group_off, w.goffp, w.Ap, w.ApT, w.flag);
+    MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(1), dim3(1024), 0, st, w.flag, s.N, touched, n_touched);
+    const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
+    ProbTokKC<true> pg{};
+    pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
+    pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
+    launch_gemm_mfma("dact_gemm", pg, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
+    if (dh) {
+      ProbTokNC ph{};
+      ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
+      ph.d = s.d; ph.part = w.part;
+      launch_gemm_mfma("dh_gemm", ph, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
+      launch_reduce_parts(s, w.part, w, dh, st);
+    }
+    const int neu_grid = kXcd * ((s.n_blocks + kXcd - 1) / kXcd) * ((s.block_size + kTM - 1) / kTM) *
+                         ((s.d + kTN - 1) / kTN);
+    ProbNeuNC pn{};
+    pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
+    pn.n_groups = s.n_blocks; pn.bs = s.block_size; pn.d = s.d;
+    pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
+    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
+    pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
+    launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
+    (void)n_ent;
+    return launch_status();
+  }
+
   if (s.dtype == MEFT_BF16) launch_gather_bwd<bf16_t>(s, K, V, dOut, idx, act, w.ds, dh, st);
   else launch_gather_bwd<float>(s, K, V, dOut, idx, act, w.ds, dh, st);
 
-  const size_t n_clear = (size_t)(w.cursor - w.cnt) + s.N;  // cnt, its padding, cursor
-  MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((n_clear + 255) / 256)), dim3(256), 0, st, w.cnt,
+  const size_t n_clear = (size_t)(w.cursor - w.cnt_n) + s.N;  // cnt, its padding, cursor
+  MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((n_clear + 255) / 256)), dim3(256), 0, st, w.cnt_n,
               n_clear, 0);
-  MEFT_LAUNCH("pair_count", pair_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.cnt);
-  MEFT_LAUNCH("pair_scan", pair_scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt, s.N, w.seg_off, touched,
+  MEFT_LAUNCH("pair_count", pair_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.cnt_n);
+  MEFT_LAUNCH("pair_scan", pair_scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt_n, s.N, w.seg_off, touched,
               n_touched);
   MEFT_LAUNCH("pair_fill", pair_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.seg_off,
               w.cursor, w.pair_list);

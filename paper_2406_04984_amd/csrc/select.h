@@ -126,12 +126,15 @@ __global__ __launch_bounds__(256) void fill_groups_kernel(const int32_t* __restr
 // are turned into ordered 32-bit keys in LDS; a most-significant-digit radix select (4 passes of
 // 8 bits) finds the key of the k-th largest and how many of its equals still belong; then one
 // ordered sweep emits the selected positions in ascending order: all keys above the threshold,
-// and the first `need` positions that equal it.
+// and the first `need` positions that equal it.  With Ap != nullptr it also writes the token's
+// dense activation rows (one per chosen block, slot-major, zero where not selected).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void topk_select_kernel(const float* __restrict__ sc,
                                                           const int32_t* __restrict__ sblk, int C, int bs,
                                                           int e, int k, int32_t* __restrict__ idx,
-                                                          float* __restrict__ act) {
+                                                          float* __restrict__ act,
+                                                          const int32_t* __restrict__ slot_of_ent, int bsp,
+                                                          uint16_t* __restrict__ Ap) {
   extern __shared__ uint32_t s_keys[];  // [C]
   __shared__ int s_hist[256];
   __shared__ int s_w[4];
@@ -190,8 +193,27 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const float* __restric
       idx[(size_t)t * k + slot] = sblk[(size_t)t * e + q] * bs + r;
       act[(size_t)t * k + slot] = v > 0.f ? v : 0.f;
     }
+    else if (Ap) s_keys[i] = 0u;  // 0 marks "not selected" for the dense row written below
     gt_before += gt;
     eq_before += eq;
+  }
+  if (Ap == nullptr) return;
+  // dense activation rows A'[slot, 0:bsp] for the matrix-core path: bf16(act) where selected, else 0
+  __syncthreads();
+  for (int q = 0; q < e; ++q) {
+    uint16_t* row = Ap + (size_t)slot_of_ent[t * e + q] * bsp;
+    for (int r = tid * 2; r < bsp; r += 512) {
+      uint32_t w = 0u;
+#pragma unroll
+      for (int z = 0; z < 2; ++z) {
+        if (r + z < bs) {
+          const uint32_t key = s_keys[q * bs + r + z];
+          const float v = key ? key_to_float(key) : 0.f;
+          w |= (v > 0.f ? f32_to_bf16_bits(v) : 0u) << (16 * z);
+        }
+      }
+      *reinterpret_cast<uint32_t*>(row + r) = w;
+    }
   }
 }
 
