@@ -41,6 +41,13 @@ def kernel_models(cfg):
         "gather_fwd": ("hbm", P * d * s + T * d * s + P * 8.0, "byte"),
         "gather_bwd": ("hbm", 2.0 * P * d * s + 2.0 * T * d * s + P * 12.0, "byte"),
         "seg_reduce": ("hbm", 2.0 * P * d * s + P * 12.0, "byte"),   # + 2*U*d*s written, U <= N
+        # block-dense path: the flop count of each contraction over the candidates of the chosen blocks
+        "value_gemm": ("mfma", 2.0 * T * C * d, "flop"),
+        "dact_gemm": ("mfma", 2.0 * T * C * d, "flop"),
+        "dh_gemm": ("mfma", 2.0 * T * C * d, "flop"),
+        "dV_gemm": ("mfma", 2.0 * T * C * d, "flop"),
+        "dK_gemm": ("mfma", 2.0 * T * C * d, "flop"),
+        "reduce_parts": ("hbm", T * cfg.top_e * d * 4.0 + T * d * s, "byte"),
     }
 
 

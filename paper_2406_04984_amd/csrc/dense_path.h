@@ -34,11 +34,12 @@ struct ProbRouter {
   }
   __device__ const uint16_t* a_row(const TileCoord&, int m) const { return h + (size_t)(m < T ? m : T - 1) * d; }
   __device__ const uint16_t* b_row(const TileCoord&, int n) const { return Wg + (size_t)(n < B ? n : B - 1) * d; }
-  __device__ void store4(const TileCoord&, int m, int n, const float (&v)[4]) const {
-    if (n >= B) return;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (m + i < T) p[(size_t)(m + i) * B + n] = v[i];
+  __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+    for (int idx = tid; idx < kTM * kTN; idx += 256) {
+      const int r = idx / kTN, c = idx - r * kTN;
+      const int m = tc.m0 + r, n = tc.n0 + c;
+      if (m < T && n < B) p[(size_t)m * B + n] = tile[tile_index(r, c)];
+    }
   }
 };
 
@@ -69,26 +70,61 @@ struct ProbTokKC {
   __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
     return W + ((size_t)tc.g * bs + (n < bs ? n : bs - 1)) * d;
   }
-  __device__ void store4(const TileCoord& tc, int m, int n, const float (&v)[4]) const {
+  __device__ void store_tile(const TileCoord& tc, float* tile, int tid) const {
     if constexpr (!MASKED) {
-      if (n >= bs) return;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (m + i < tc.Mrows) sc[(size_t)perm[tc.slot0 + m + i] * bs + n] = v[i];
-    } else {
-      const int Mgp = round_up64(tc.Mrows);
-      uint32_t b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool in = (m + i < tc.Mrows) && (n < bs);
-        const size_t at = (size_t)(tc.slot0 + (in ? m + i : 0)) * bsp + (in ? n : 0);
-        const bool on = in && (Ap[at] & 0x7FFFu) != 0 && !(Ap[at] & 0x8000u);
-        b[i] = on ? f32_to_bf16_bits(v[i]) : 0u;
-        if (m + i < tc.Mrows && n < bsp) DS[(size_t)(tc.slot0 + m + i) * bsp + n] = (uint16_t)b[i];
+      // a wave stores one row per step: 64 lanes x 4 floats = the 256 columns of the tile
+      const int c = (tid & 63) * 4, n = tc.n0 + c;
+      for (int r = tid >> 6; r < kTM; r += 4) {
+        const int m = tc.m0 + r;
+        if (m >= tc.Mrows) break;
+        float* dst = sc + (size_t)perm[tc.slot0 + m] * bs + n;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+        if ((bs & 3) == 0) {
+          if (n < bs) *reinterpret_cast<f32x4*>(dst) = v;
+        } else {
+          const float x[4] = {v.x, v.y, v.z, v.w};
+          for (int z = 0; z < 4; ++z)
+            if (n + z < bs) dst[z] = x[z];
+        }
       }
-      if (n < bs && m < Mgp) {
-        uint2 w = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
-        *reinterpret_cast<uint2*>(DST + ((size_t)goffp[tc.g] * bs + (size_t)n * Mgp + m)) = w;
+    } else {
+      // pass 1, slot-major: rows of 8 columns; mask by A' > 0, store DS', keep the masked value in the tile
+      const int c = (tid & 31) * 8, n = tc.n0 + c;
+      for (int r = tid >> 5; r < kTM; r += 8) {
+        const int m = tc.m0 + r;
+        const bool row_in = m < tc.Mrows;
+        float x[8];
+        {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+          const f32x4 b = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c + 4)]);
+          x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+        }
+        u32x4 mk = {0u, 0u, 0u, 0u};
+        if (row_in && n < bsp) mk = *reinterpret_cast<const u32x4*>(Ap + (size_t)(tc.slot0 + m) * bsp + n);
+        const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+#pragma unroll
+        for (int z = 0; z < 8; ++z) {
+          const uint32_t a16 = (mw[z >> 1] >> (16 * (z & 1))) & 0xFFFFu;
+          const bool on = (a16 & 0x7FFFu) != 0u && (a16 & 0x8000u) == 0u;   // positive, non-zero activation
+          x[z] = on ? x[z] : 0.f;
+        }
+        if (row_in && n < bsp) Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(DS) + (size_t)(tc.slot0 + m) * bsp + n, x);
+        f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
+        *reinterpret_cast<f32x4*>(&tile[tile_index(r, c)]) = a;
+        *reinterpret_cast<f32x4*>(&tile[tile_index(r, c + 4)]) = b;
+      }
+      __syncthreads();
+      // pass 2, neuron-major: column n, 8 consecutive slots -> one 16-byte store into DS'^T
+      const int Mgp = round_up64(tc.Mrows);
+      uint16_t* base = DST + (size_t)goffp[tc.g] * bs;
+      for (int idx = tid; idx < kTN * (kTM / 8); idx += 256) {
+        const int cc = idx & (kTN - 1), r8 = (idx >> 8) * 8;   // kTN == 256
+        const int nn = tc.n0 + cc, m = tc.m0 + r8;
+        if (nn >= bs || m >= Mgp) continue;
+        float x[8];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) x[z] = tile[tile_index(r8 + z, cc)];
+        Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(base) + (size_t)nn * Mgp + m, x);
       }
     }
   }
@@ -116,11 +152,15 @@ struct ProbTokNC {
   __device__ const uint16_t* b_row(const TileCoord& tc, int k) const {
     return W + ((size_t)tc.g * bs + (k < bs ? k : bs - 1)) * d;
   }
-  __device__ void store4(const TileCoord& tc, int m, int n, const float (&v)[4]) const {
-    if (n >= d) return;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (m + i < tc.Mrows) part[(size_t)(tc.slot0 + m + i) * d + n] = v[i];
+  __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+    const int c = (tid & 63) * 4, n = tc.n0 + c;
+    if (n >= d) return;   // d % 64 == 0: a float4 is fully in or out
+    for (int r = tid >> 6; r < kTM; r += 4) {
+      const int m = tc.m0 + r;
+      if (m >= tc.Mrows) break;
+      *reinterpret_cast<f32x4*>(part + (size_t)(tc.slot0 + m) * d + n) =
+          *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+    }
   }
 };
 
@@ -157,15 +197,18 @@ struct ProbNeuNC {
         reinterpret_cast<uintptr_t>(tok_of_slot));
     return X + (size_t)tos[tc.slot0 + (k < tc.aux ? k : tc.aux - 1)] * d;
   }
-  __device__ void store4(const TileCoord& tc, int m, int n, const float (&v)[4]) const {
-    if (n >= d) return;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = m + i;
-      if (r < bs) {
-        const size_t j = (size_t)tc.g * bs + r;
-        if (flag[j] > 0) G[j * d + n] = (uint16_t)f32_to_bf16_bits(v[i]);
-      }
+  __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+    const int c = (tid & 31) * 8, n = tc.n0 + c;
+    if (n >= d) return;   // d % 64 == 0: a group of 8 columns is fully in or out
+    for (int r = tid >> 5; r < kTM; r += 8) {
+      const int m = tc.m0 + r;
+      if (m >= bs) break;
+      const size_t j = (size_t)tc.g * bs + m;
+      if (flag[j] <= 0) continue;
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c + 4)]);
+      const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(G) + j * d + n, x);
     }
   }
 };

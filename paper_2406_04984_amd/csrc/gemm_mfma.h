@@ -52,13 +52,16 @@ struct TileCoord {
 //   __device__ bool locate(int wg, TileCoord&) const;   false: no tile for this workgroup
 //   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
 //   __device__ const uint16_t* b_row(const TileCoord&, int r) const;   KC: row n; NC: row k (clamped)
-//   __device__ void store4(const TileCoord&, int m, int n, const float (&v)[4]) const;  rows m..m+3 of column n
+//   __device__ void store_tile(const TileCoord&, float* tile, int tid) const;   write the finished tile (in LDS)
 //
-// Epilogue contract: acc[i][j][r] of a wave holds C[m][n] with
-//   m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,   n = wn + j*32 + lane%32   (tile-local).
-// store4 receives, per (i, j, r/4), four consecutive rows of one column.
+// acc[i][j][r] of a wave holds C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,
+// n = wn + j*32 + lane%32 (tile-local); the kernel lays the tile out row-major in LDS (tile_index) and hands
+// it to store_tile, which all 256 threads of the workgroup execute.
 
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// index of element (m, n) of the fp32 epilogue tile in LDS (see the epilogue of gemm_mfma_kernel)
+__device__ __forceinline__ int tile_index(int m, int n) { return m * kTN + (n ^ (((m >> 2) & 1) << 7)); }
 
 // Eight transposing LDS reads (the four n-contiguous B fragments of one k16 step, low and high k half)
 // followed by the wait for them.  Written as one asm block: issued through the builtin, the compiler
@@ -222,18 +225,24 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p) {
     stage = stage + 1 == kStages ? 0 : stage + 1;
   }
 
+  // ---- epilogue: the 128 x 256 fp32 tile goes through LDS so that the policy can store whole rows with
+  // 16-byte accesses.  Layout: row-major, 256 floats per row, the two 128-float halves of a row swapped
+  // when (row >> 2) is odd, which keeps the two half-waves of an accumulator write in different banks.
+  __syncthreads();  // every wave is done reading the last operand stage
+  float* tile = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int n = tc.n0 + wn + j * 32 + fr;
+      const int n = wn + j * 32 + fr;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int m = tc.m0 + wm + i * 32 + q * 8 + fc * 4;
-        const float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-        p.store4(tc, m, n, v);  // rows m..m+3 of column n
+      for (int r = 0; r < 16; ++r) {
+        const int m = wm + i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3);
+        tile[tile_index(m, n)] = acc[i][j][r];
       }
     }
+  __syncthreads();
+  p.store_tile(tc, tile, tid);
 }
 
 // ---- tile schedule shared by the token-major problems ----------------------------------------
