@@ -36,12 +36,54 @@ def test_config_small_bf16(P):
     rep.assert_ok()
 
 
+def _full_size(P, name, n_rows=384):
+    """The benchmark's launch configuration at full size: every token's selections, out and dh against the
+    oracle; dK / dV on a seeded sample of neuron rows (the oracle computes those rows one by one)."""
+    cfg = synth.CONFIGS[name]
+    rows = np.sort(np.random.default_rng(cfg.seed).choice(cfg.N, size=n_rows, replace=False)).astype(np.int32)
+    rep = P.run_and_compare(cfg, rows=rows)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+
+
+@pytest.mark.timeout(900)
+def test_config_llama7b_bf16_full_size(P):
+    _full_size(P, "llama7b_bf16")
+
+
+@pytest.mark.timeout(900)
+def test_config_wide_bf16_full_size(P):
+    _full_size(P, "wide_bf16")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ragged_shapes(P, dtype):
     # token count, block size, hidden size and candidate count all off the tile sizes
     _case(P, T=77, d=72, n_blocks=5, block_size=40, top_e=3, top_k=17, dtype=dtype, seed=101)
     _case(P, T=300, d=200, n_blocks=7, block_size=150, top_e=2, top_k=33, dtype=dtype, seed=102)
     _case(P, T=130, d=2056, n_blocks=3, block_size=24, top_e=2, top_k=9, dtype=dtype, seed=103)
+
+
+def test_ragged_shapes_on_the_matrix_core_path(P):
+    """bf16 shapes that take the block-dense path (hidden size a multiple of 64) with token groups, block
+    sizes and hidden sizes off the 128 x 256 x 64 tile, an empty block, and one block taking every token."""
+    _case(P, T=333, d=192, n_blocks=5, block_size=72, top_e=2, top_k=19, dtype="bf16", seed=701)
+    _case(P, T=130, d=320, n_blocks=3, block_size=300, top_e=3, top_k=100, dtype="bf16", seed=702)
+    _case(P, T=700, d=64, n_blocks=20, block_size=16, top_e=5, top_k=40, dtype="bf16", seed=703)
+    _case(P, T=257, d=512, n_blocks=2, block_size=520, top_e=1, top_k=65, dtype="bf16", seed=704)
+    _case(P, T=90, d=64, n_blocks=4, block_size=30, top_e=2, top_k=12, dtype="bf16", seed=706)
+    cfg = synth.small_case(T=200, d=128, n_blocks=6, block_size=64, top_e=2, top_k=24, dtype="bf16", seed=705)
+    t = synth.make_inputs(cfg)
+    t.bias = np.array([0, 50, -50, 0, 0, 0], np.float32)     # block 1 takes every token, block 2 none
+    from oracle import oracle
+    g = P.run_gpu(t)
+    r = oracle.route(t.h, t.Wg, cfg.top_e, t.bias)
+    f = oracle.forward(t.h, t.K, t.V, r.block_idx, cfg.block_size, cfg.top_k, want_candidates=True)
+    b = oracle.backward(t.h, t.K, t.V, f.idx, f.score, t.dOut, cfg.block_size)
+    rep = P.compare(t, g, r, f, b)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+    assert (g["block_idx"][:, 0] == 1).all() and (g["block_idx"] != 2).all()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
