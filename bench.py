@@ -59,6 +59,7 @@ def main() -> int:
     ap.add_argument("--config", default="llama7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--verify", action="store_true", help="check structural invariants of one step first")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the layer shards by token across GPUs only on paper "
@@ -81,6 +82,16 @@ def main() -> int:
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
+    if args.verify:
+        # one step checked against invariants that hold at any size, before anything is timed
+        layer.fill_grad_sentinel()
+        layer.step()
+        torch.cuda.synchronize()
+        nt = int(layer.n_touched.item())
+        uniq = torch.unique(layer.idx)
+        assert nt == uniq.numel() and torch.equal(layer.touched[:nt].long(), uniq), "touched != unique(idx)"
+        assert bool((layer.idx[:, 1:] > layer.idx[:, :-1]).all()), "idx rows not strictly ascending"
+        assert bool(torch.isfinite(layer.out.float()).all()) and bool(torch.isfinite(layer.dh.float()).all())
     for _ in range(args.warmup):
         layer.step()
     torch.cuda.synchronize()

@@ -15,6 +15,7 @@
 // A'[slot, r] = bf16(act) where neuron r of the block is selected by the slot's token, else 0.
 #pragma once
 #include "gemm_mfma.h"
+#include "select.h"
 
 namespace meft {
 
@@ -331,25 +332,43 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restri
   }
 }
 
-// touched = ascending ids with flag > 0 (one workgroup of 1024).
-__global__ __launch_bounds__(1024) void compact_flags_kernel(const int32_t* __restrict__ flag, int N,
-                                                             int32_t* __restrict__ touched,
-                                                             int32_t* __restrict__ n_touched) {
-  __shared__ int s_f[16];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int chunk = (N + 1023) / 1024;
-  const int j0 = min(N, tid * chunk), j1 = min(N, j0 + chunk);
+// touched = ascending ids with flag > 0, in two launches over chunks of kFlagChunk flags:
+// per-chunk counts, then every chunk sums the counts before it and writes its ids in order.
+constexpr int kFlagChunk = 2048;
+
+__global__ __launch_bounds__(256) void count_flags_kernel(const int32_t* __restrict__ flag, int N,
+                                                          int32_t* __restrict__ chunk_cnt) {
+  __shared__ int s_w[4];
+  const int j0 = blockIdx.x * kFlagChunk + threadIdx.x * (kFlagChunk / 256);
   int f = 0;
-  for (int j = j0; j < j1; ++j) f += flag[j] > 0;
-  const int fi = wave_incl_scan(f);
-  if (lane == 63) s_f[w] = fi;
-  __syncthreads();
-  int fb = 0;
-  for (int i = 0; i < w; ++i) fb += s_f[i];
-  int nt = fb + fi - f;
-  for (int j = j0; j < j1; ++j)
-    if (flag[j] > 0) touched[nt++] = j;
-  if (tid == 1023) *n_touched = nt;
+#pragma unroll
+  for (int z = 0; z < kFlagChunk / 256; ++z)
+    if (j0 + z < N) f += flag[j0 + z] > 0;
+  int tot;
+  block_excl_scan_256(f, s_w, tot);
+  if (threadIdx.x == 0) chunk_cnt[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(256) void compact_flags_kernel(const int32_t* __restrict__ flag, int N,
+                                                            const int32_t* __restrict__ chunk_cnt,
+                                                            int32_t* __restrict__ touched,
+                                                            int32_t* __restrict__ n_touched) {
+  __shared__ int s_w[4];
+  int before = 0;
+  for (int c = threadIdx.x; c < (int)blockIdx.x; c += 256) before += chunk_cnt[c];
+  int base;
+  block_excl_scan_256(before, s_w, base);   // base = number of touched ids in earlier chunks
+  const int j0 = blockIdx.x * kFlagChunk + threadIdx.x * (kFlagChunk / 256);
+  int f = 0;
+#pragma unroll
+  for (int z = 0; z < kFlagChunk / 256; ++z)
+    if (j0 + z < N) f += flag[j0 + z] > 0;
+  int tot;
+  int pos = base + block_excl_scan_256(f, s_w, tot);
+#pragma unroll
+  for (int z = 0; z < kFlagChunk / 256; ++z)
+    if (j0 + z < N && flag[j0 + z] > 0) touched[pos++] = j0 + z;
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) *n_touched = base + tot;
 }
 
 }  // namespace meft

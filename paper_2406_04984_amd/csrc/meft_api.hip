@@ -152,19 +152,20 @@ struct BwdWs : DispatchWs {
   float* ds;
   int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted;
   // dense path
-  int32_t* flag;
+  int32_t *flag, *chunk_cnt;
   uint16_t *Ap, *ApT, *DS, *DST;
   float* part;
   size_t bytes;
   BwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
     const size_t P = (size_t)s.T * s.top_k;
-    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = flag = nullptr;
+    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = flag = chunk_cnt = nullptr;
     Ap = ApT = DS = DST = nullptr; part = nullptr;
     if (use_dense(s)) {
       carve(s, c);
       const size_t n_ent = (size_t)s.T * s.top_e;
       const size_t slots_p = n_ent + (size_t)64 * s.n_blocks;   // group sizes padded to 64
+      chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
       flag = c.take<int32_t>(s.N);
       Ap = c.take<uint16_t>(n_ent * round64(s.block_size));      // Ap and ApT adjacent: cleared by one fill
       ApT = c.take<uint16_t>(slots_p * s.block_size);
@@ -268,8 +269,8 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
 void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, hipStream_t st) {
   const int n_ent = s.T * s.top_e;
-  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(256), 0, st, w.sblk, n_ent, w.cnt);
-  MEFT_LAUNCH("fill_groups", fill_groups_kernel, dim3(s.n_blocks), dim3(256), 0, st, w.sblk, n_ent, w.cnt,
+  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, n_ent, w.cnt);
+  MEFT_LAUNCH("fill_groups", fill_groups_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, n_ent, w.cnt,
               s.n_blocks, BM, w.group_off, w.tile_off, w.perm);
   if (dense) {
     MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
@@ -428,7 +429,10 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
                 clear_words, 0);
     MEFT_LAUNCH("scatter_act", scatter_act_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, act, P, s.top_k,
                 s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.group_off, w.goffp, w.Ap, w.ApT, w.flag);
-    MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(1), dim3(1024), 0, st, w.flag, s.N, touched, n_touched);
+    const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
+    MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
+    MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
+                touched, n_touched);
     const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
     ProbTokKC<true> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;

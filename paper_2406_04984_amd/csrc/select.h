@@ -75,33 +75,59 @@ __device__ __forceinline__ int block_excl_scan_256(int v, int* s_wave /*[4]*/, i
   return base + incl - v;
 }
 
-// (2) cnt[b] = number of entries of block b.  One workgroup per block.
-__global__ __launch_bounds__(256) void count_blocks_kernel(const int32_t* __restrict__ sblk, int n_ent,
-                                                           int32_t* __restrict__ cnt) {
-  __shared__ int s_w[4];
-  const int b = blockIdx.x;
-  int c = 0;
-  for (int i = threadIdx.x; i < n_ent; i += 256) c += (sblk[i] == b);
-  c = wave_sum_i(c);
-  if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = c;
+// exclusive scan of one int per thread over a 1024-thread workgroup
+__device__ __forceinline__ int block_excl_scan_1024(int v, int* s_wave /*[16]*/, int& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int incl = wave_incl_scan(v);
+  if (lane == 63) s_wave[w] = incl;
   __syncthreads();
-  if (threadIdx.x == 0) cnt[b] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { const int x = s_wave[i]; base += (i < w) ? x : 0; tot += x; }
+  total = tot;
+  __syncthreads();
+  return base + incl - v;
+}
+
+// number of entries equal to b among sblk[i0, i1); 16-byte loads where the range allows
+__device__ __forceinline__ int count_eq(const int32_t* __restrict__ sblk, int i0, int i1, int b) {
+  int c = 0, i = i0;
+  for (; i < i1 && (i & 3); ++i) c += (sblk[i] == b);
+  for (; i + 4 <= i1; i += 4) {
+    const int4 v = *reinterpret_cast<const int4*>(sblk + i);
+    c += (v.x == b) + (v.y == b) + (v.z == b) + (v.w == b);
+  }
+  for (; i < i1; ++i) c += (sblk[i] == b);
+  return c;
+}
+
+// (2) cnt[b] = number of entries of block b.  One workgroup of 1024 threads per block; every thread counts
+// a contiguous chunk.
+__global__ __launch_bounds__(1024) void count_blocks_kernel(const int32_t* __restrict__ sblk, int n_ent,
+                                                            int32_t* __restrict__ cnt) {
+  __shared__ int s_w[16];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int chunk = (n_ent + 1023) / 1024;
+  const int i0 = min(n_ent, tid * chunk), i1 = min(n_ent, i0 + chunk);
+  int tot;
+  block_excl_scan_1024(count_eq(sblk, i0, i1, b), s_w, tot);
+  if (tid == 0) cnt[b] = tot;
 }
 
 // (3) group_off / tile_off (prefix sums over blocks of cnt and of ceil(cnt/BM)) and the stable
 // fill perm[group_off[b] + rank] = entry, entries of a block in ascending entry order.
-__global__ __launch_bounds__(256) void fill_groups_kernel(const int32_t* __restrict__ sblk, int n_ent,
-                                                          const int32_t* __restrict__ cnt, int B, int BM,
-                                                          int32_t* __restrict__ group_off,
-                                                          int32_t* __restrict__ tile_off,
-                                                          int32_t* __restrict__ perm) {
-  __shared__ int s_w[4];
+__global__ __launch_bounds__(1024) void fill_groups_kernel(const int32_t* __restrict__ sblk, int n_ent,
+                                                           const int32_t* __restrict__ cnt, int B, int BM,
+                                                           int32_t* __restrict__ group_off,
+                                                           int32_t* __restrict__ tile_off,
+                                                           int32_t* __restrict__ perm) {
+  __shared__ int s_w[16];
   const int b = blockIdx.x, tid = threadIdx.x;
   int go = 0, to = 0;
-  for (int i = tid; i < b; i += 256) { const int c = cnt[i]; go += c; to += (c + BM - 1) / BM; }
+  for (int i = tid; i < b; i += 1024) { const int c = cnt[i]; go += c; to += (c + BM - 1) / BM; }
   int tot_g, tot_t;
-  block_excl_scan_256(go, s_w, tot_g);
-  block_excl_scan_256(to, s_w, tot_t);
+  block_excl_scan_1024(go, s_w, tot_g);
+  block_excl_scan_1024(to, s_w, tot_t);
   if (tid == 0) {
     group_off[b] = tot_g;
     tile_off[b] = tot_t;
@@ -110,12 +136,10 @@ __global__ __launch_bounds__(256) void fill_groups_kernel(const int32_t* __restr
       tile_off[B] = tot_t + (cnt[b] + BM - 1) / BM;
     }
   }
-  const int chunk = (n_ent + 255) / 256;
-  const int i0 = tid * chunk, i1 = min(n_ent, i0 + chunk);
-  int c = 0;
-  for (int i = i0; i < i1; ++i) c += (sblk[i] == b);
+  const int chunk = (n_ent + 1023) / 1024;
+  const int i0 = min(n_ent, tid * chunk), i1 = min(n_ent, i0 + chunk);
   int tot;
-  int rank = block_excl_scan_256(c, s_w, tot);
+  int rank = block_excl_scan_1024(count_eq(sblk, i0, i1, b), s_w, tot);
   for (int i = i0; i < i1; ++i)
     if (sblk[i] == b) perm[tot_g + rank++] = i;
 }
