@@ -47,7 +47,7 @@ def kernel_models(cfg):
         "dh_gemm": ("mfma", 2.0 * T * C * d, "flop"),
         "dV_gemm": ("mfma", 2.0 * T * C * d, "flop"),
         "dK_gemm": ("mfma", 2.0 * T * C * d, "flop"),
-        "reduce_parts": ("hbm", T * cfg.top_e * d * 4.0 + T * d * s, "byte"),
+        "reduce_parts": ("hbm", T * cfg.top_e * d * 2.0 + T * d * s, "byte"),
     }
 
 

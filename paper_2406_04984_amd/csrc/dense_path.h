@@ -6,7 +6,7 @@
 //
 // Per block b with its token group G_b (slots, ascending token order), block_size neurons, hidden d:
 //   scores   S [G_b, bs] = h[G_b, :] . K_b^T                     (Eq. 6)            KC GEMM
-//   forward  part[G_b, d] = A'[G_b, bs] . V_b                    (Eq. 4, one block) NC GEMM
+//   forward  part[G_b, d] = A'[G_b, bs] . V_b  (stored bf16)     (Eq. 4, one block) NC GEMM
 //            out[t, :] = sum over the token's blocks of part      (row reduce)
 //   backward G [G_b, bs] = dOut[G_b, :] . V_b^T, DS' = G * [A' > 0]                 KC GEMM
 //            dhpart[G_b, d] = DS'[G_b, bs] . K_b ; dh = row reduce                 NC GEMM
@@ -23,23 +23,32 @@ __device__ __forceinline__ int round_up64(int v) { return (v + 63) & ~63; }
 
 // ---- problem policies for gemm_mfma_kernel ----------------------------------------------------
 
-// Router scores (Eq. 5): p[T, n_blocks] = h . Wg^T, one group.
+// Router scores (Eq. 5): p[T, n_blocks] = h . Wg^T, one group.  The problem is skinny (n_blocks columns), so
+// the contraction is split `ksplit` ways over workgroups to fill the chip; split s writes its partial
+// scores to p + s*T*n_blocks and the top-e kernel adds the partials in a fixed order.
 struct ProbRouter {
   static constexpr bool kBNC = false;
   const uint16_t* h; const uint16_t* Wg; float* p;
-  int T, d, B;
+  int T, d, B, ksplit;
   __device__ bool locate(int wg, TileCoord& tc) const {
-    const int tn = (B + kTN - 1) / kTN, mt = wg / tn;
-    tc.g = 0; tc.m0 = mt * kTM; tc.n0 = (wg - mt * tn) * kTN; tc.Mrows = T; tc.Ncols = B; tc.nk = d / kTK; tc.slot0 = 0;
+    const int tn = (B + kTN - 1) / kTN;
+    const int ks = wg % ksplit, w = wg / ksplit, mt = w / tn;
+    tc.g = 0; tc.m0 = mt * kTM; tc.n0 = (w - mt * tn) * kTN; tc.Mrows = T; tc.Ncols = B;
+    tc.nk = d / kTK / ksplit; tc.slot0 = 0; tc.aux = ks;
     return tc.m0 < T;
   }
-  __device__ const uint16_t* a_row(const TileCoord&, int m) const { return h + (size_t)(m < T ? m : T - 1) * d; }
-  __device__ const uint16_t* b_row(const TileCoord&, int n) const { return Wg + (size_t)(n < B ? n : B - 1) * d; }
+  __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
+    return h + (size_t)(m < T ? m : T - 1) * d + (size_t)tc.aux * tc.nk * kTK;
+  }
+  __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
+    return Wg + (size_t)(n < B ? n : B - 1) * d + (size_t)tc.aux * tc.nk * kTK;
+  }
   __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+    float* dst = p + (size_t)tc.aux * T * B;
     for (int idx = tid; idx < kTM * kTN; idx += 256) {
       const int r = idx / kTN, c = idx - r * kTN;
       const int m = tc.m0 + r, n = tc.n0 + c;
-      if (m < T && n < B) p[(size_t)m * B + n] = tile[tile_index(r, c)];
+      if (m < T && n < B) dst[(size_t)m * B + n] = tile[tile_index(r, c)];
     }
   }
 };
@@ -140,7 +149,7 @@ struct ProbTokNC {
   const int32_t* group_off;
   TokenSched sched;
   int bs, bsp, d;
-  float* part;                // [slots, d]
+  uint16_t* part;             // [slots, d] bf16: one block's contribution to a token's row
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
     if (!locate_token_tile(sched, group_off, wg, (d + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
@@ -154,13 +163,15 @@ struct ProbTokNC {
     return W + ((size_t)tc.g * bs + (k < bs ? k : bs - 1)) * d;
   }
   __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
-    const int c = (tid & 63) * 4, n = tc.n0 + c;
-    if (n >= d) return;   // d % 64 == 0: a float4 is fully in or out
-    for (int r = tid >> 6; r < kTM; r += 4) {
+    const int c = (tid & 31) * 8, n = tc.n0 + c;
+    if (n >= d) return;   // d % 64 == 0: a group of 8 columns is fully in or out
+    for (int r = tid >> 5; r < kTM; r += 8) {
       const int m = tc.m0 + r;
       if (m >= tc.Mrows) break;
-      *reinterpret_cast<f32x4*>(part + (size_t)(tc.slot0 + m) * d + n) =
-          *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c + 4)]);
+      const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(part) + (size_t)(tc.slot0 + m) * d + n, x);
     }
   }
 };
@@ -299,9 +310,9 @@ __global__ void scatter_act_kernel(const int32_t* __restrict__ idx, const float*
   ApT[(size_t)goffp[b] * bs + (size_t)r * Mgp + (slot - s0)] = v;
 }
 
-// out[t, :] = sum over the token's entries of part[slot(entry), :], rounded once to bf16.
+// out[t, :] = sum over the token's entries of part[slot(entry), :] (bf16 partials, fp32 sum), rounded to bf16.
 template <int NV>
-__global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ part,
+__global__ __launch_bounds__(256) void reduce_parts_kernel(const uint16_t* __restrict__ part,
                                                            const int32_t* __restrict__ sblk,
                                                            const int32_t* __restrict__ slot_of_ent, int d, int e,
                                                            uint16_t* __restrict__ out) {
@@ -313,13 +324,13 @@ __global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restri
     for (int c = 0; c < 8; ++c) acc[v][c] = 0.f;
   for (int q = 0; q < e; ++q) {
     if (sblk[(size_t)t * e + q] < 0) continue;
-    const float* row = part + (size_t)slot_of_ent[t * e + q] * d;
+    const bf16_t* row = reinterpret_cast<const bf16_t*>(part) + (size_t)slot_of_ent[t * e + q] * d;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       const int col = (tid + v * nthr) * 8;
       if (col < d) {
         float x[8];
-        Vec8<float>::load(row + col, x);
+        Vec8<bf16_t>::load(row + col, x);
 #pragma unroll
         for (int c = 0; c < 8; ++c) acc[v][c] += x[c];
       }

@@ -98,12 +98,14 @@ bool use_dense(const meft_shape& s) {
 int round64(int v) { return (v + 63) & ~63; }
 int sched_cap(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + (s.n_blocks + kXcd - 1) / kXcd + 1); }
 
+constexpr int kRouterSplitMax = 4;
+
 struct RouteWs {
   float* p;
   size_t bytes;
   RouteWs(const meft_shape& s, void* ws) {
     Carver c(ws);
-    p = c.take<float>((size_t)s.T * s.n_blocks);
+    p = c.take<float>((size_t)kRouterSplitMax * s.T * s.n_blocks);
     bytes = c.off;
   }
 };
@@ -131,7 +133,7 @@ struct DispatchWs {
 struct FwdWs : DispatchWs {
   float* sc;
   uint16_t* Ap;   // dense path: A' [T*e, bsp]
-  float* part;    // dense path: per-entry partial outputs [T*e, d]
+  uint16_t* part; // dense path: per-entry partial outputs [T*e, d] bf16
   size_t bytes;
   FwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
@@ -141,7 +143,7 @@ struct FwdWs : DispatchWs {
     Ap = nullptr; part = nullptr;
     if (use_dense(s)) {
       Ap = c.take<uint16_t>(n_ent * round64(s.block_size));
-      part = c.take<float>(n_ent * s.d);
+      part = c.take<uint16_t>(n_ent * s.d);
     }
     bytes = c.off;
   }
@@ -153,8 +155,7 @@ struct BwdWs : DispatchWs {
   int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted;
   // dense path
   int32_t *flag, *chunk_cnt;
-  uint16_t *Ap, *ApT, *DS, *DST;
-  float* part;
+  uint16_t *Ap, *ApT, *DS, *DST, *part;
   size_t bytes;
   BwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
@@ -171,7 +172,7 @@ struct BwdWs : DispatchWs {
       ApT = c.take<uint16_t>(slots_p * s.block_size);
       DS = c.take<uint16_t>(n_ent * round64(s.block_size));
       DST = c.take<uint16_t>(slots_p * s.block_size);
-      part = c.take<float>(n_ent * s.d);
+      part = c.take<uint16_t>(n_ent * s.d);
     } else {
       ds = c.take<float>(P);
       cnt_n = c.take<int32_t>(s.N);     // cnt_n and cursor are adjacent: cleared by one fill
@@ -281,7 +282,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
 }
 
 template <int NVDUMMY = 0>
-void launch_reduce_parts(const meft_shape& s, const float* part, const DispatchWs& w, void* out, hipStream_t st) {
+void launch_reduce_parts(const meft_shape& s, const uint16_t* part, const DispatchWs& w, void* out, hipStream_t st) {
   int nthr, nv;
   row_launch(s.d, nthr, nv);
   uint16_t* o = static_cast<uint16_t*>(out);
@@ -325,10 +326,13 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  int n_part = 1;
 
   if (s.dtype == MEFT_BF16 && s.d % kTK == 0) {
-    ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), w.p, s.T, s.d, s.n_blocks};
-    launch_gemm_mfma("router_gemm", pr, ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
+    const int kt = s.d / kTK;
+    n_part = kt % 4 == 0 ? 4 : (kt % 2 == 0 ? 2 : 1);
+    ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), w.p, s.T, s.d, s.n_blocks, n_part};
+    launch_gemm_mfma("router_gemm", pr, n_part * ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
   } else {
     GemmNTArgs a{};
     a.A = h; a.Bm = Wg; a.C = w.p; a.perm = nullptr; a.group_off = nullptr; a.tile_off = nullptr;
@@ -336,7 +340,8 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
     a.e = 1;
     launch_gemm_nt(s, a, (s.T + kGemmBM - 1) / kGemmBM, (s.T + kGemmF32BM - 1) / kGemmF32BM, "router_gemm", st);
   }
-  MEFT_LAUNCH("route_topk", route_topk_kernel, dim3(s.T), dim3(64), (size_t)s.n_blocks * 4, st, w.p, bias,
+  MEFT_LAUNCH("route_topk", route_topk_kernel, dim3(s.T), dim3(64), (size_t)s.n_blocks * 4, st, w.p, n_part,
+              (size_t)s.T * s.n_blocks, bias,
               s.n_blocks, s.top_e, block_idx, block_score);
   return launch_status();
 }

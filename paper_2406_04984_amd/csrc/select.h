@@ -10,9 +10,9 @@ namespace meft {
 // Top-e blocks (Algorithm 1: tau <- TopK(p, number of experts)).  One wave per token.  The row of
 // B scores sits in LDS as ordered keys; e rounds of a wave-wide arg-max, the winner is retired
 // by zeroing its key (a live key is never 0 for finite scores).  Output order: score descending,
-// block id ascending.
+// block id ascending.  The scores may arrive as n_part partial sums, part_stride floats apart.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void route_topk_kernel(const float* __restrict__ p,
+__global__ __launch_bounds__(64) void route_topk_kernel(const float* __restrict__ p, int n_part, size_t part_stride,
                                                         const float* __restrict__ bias, int B, int e,
                                                         int32_t* __restrict__ block_idx,
                                                         float* __restrict__ block_score) {
@@ -21,6 +21,7 @@ __global__ __launch_bounds__(64) void route_topk_kernel(const float* __restrict_
   const float* row = p + (size_t)t * B;
   for (int b = lane; b < B; b += kWave) {
     float v = row[b];
+    for (int s = 1; s < n_part; ++s) v += row[s * part_stride + b];   // partial scores of a split contraction
     if (bias) v += bias[b];
     s_key[b] = order_key(v);
   }
