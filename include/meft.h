@@ -26,7 +26,7 @@
  *
  * Conventions for every entry point
  *  - All tensor pointers are DEVICE pointers owned by the caller, row-major, contiguous, 16-byte
- *    aligned.  With MEFT_FLAG_HOST_KV set, K, V, dK, dV are pinned HOST pointers instead.
+ *    aligned.  With MEFT_FLAG_HOST_KV set, K, V, dK, dV are pinned HOST pointers instead (see the flag).
  *  - `ws` is a device workspace of at least meft_workspace_bytes(shape) bytes, 256-byte aligned,
  *    owned by the caller; its contents are scratch and carry nothing from call to call.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on
@@ -58,7 +58,19 @@ typedef enum {
 
 typedef enum { MEFT_F32 = 0, MEFT_BF16 = 1 } meft_dtype;
 
-enum { MEFT_FLAG_HOST_KV = 1u }; /* K, V (and dK, dV) are pinned-host pointers */
+/*
+ * MEFT_FLAG_HOST_KV: the paper's placement of the adapter (Section 1 and Figure "Overview": parameters in CPU
+ * memory, activated parts moved to the GPU on demand).  K, V (forward, backward) and dK, dV (backward) are
+ * then PINNED HOST pointers (hipHostMalloc or equivalent).  The forward copies the blocks that some token
+ * was routed to, the backward the blocks that hold a selected neuron, with hipMemcpyAsync on a stream of the
+ * library's own, overlapped with the dispatch kernels (K) and with scoring and selection (V); the backward
+ * computes dK, dV into device staging and a kernel then writes only the touched rows over the host link.
+ * The workspace grows by four [N, d] matrices.  Differences from the conventions below, for these calls only:
+ * the host blocks once per call until the routing result (which blocks are in use) is known; the library
+ * creates one side stream, four events and a small pinned buffer on first use and keeps them; two such calls
+ * must not be in flight at the same time on different streams.
+ */
+enum { MEFT_FLAG_HOST_KV = 1u };
 
 /*
  * Problem shape.  Requirements (else MEFT_ERR_INVALID_ARG):

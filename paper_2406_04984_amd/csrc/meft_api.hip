@@ -68,7 +68,6 @@ meft_status check_shape(const meft_shape* s) {
   if (s->activation != 0) return MEFT_ERR_INVALID_ARG;
   if (s->flags & ~(uint32_t)MEFT_FLAG_HOST_KV) return MEFT_ERR_INVALID_ARG;
   if (s->d % 8 != 0 || s->d > kMaxD || C > kMaxC || s->n_blocks > kMaxBlocks) return MEFT_ERR_UNSUPPORTED;
-  if (s->flags & MEFT_FLAG_HOST_KV) return MEFT_ERR_UNSUPPORTED;
   return MEFT_OK;
 }
 
@@ -185,10 +184,81 @@ struct BwdWs : DispatchWs {
   }
 };
 
-size_t workspace_bytes(const meft_shape& s) {
+size_t compute_bytes(const meft_shape& s) {
   const size_t a = RouteWs(s, nullptr).bytes, b = FwdWs(s, nullptr).bytes, c = BwdWs(s, nullptr).bytes;
   const size_t m = a > b ? (a > c ? a : c) : (b > c ? b : c);
   return m < 256 ? 256 : m;
+}
+
+// With MEFT_FLAG_HOST_KV the workspace also holds device copies of K, V and device staging for dK, dV.
+struct HostKvWs {
+  char *Kd, *Vd, *dKd, *dVd;
+  int32_t *pair_blk, *pair_blk_cnt;   // backward: block of every pair, pairs per block
+  size_t bytes;
+  HostKvWs(const meft_shape& s, void* ws) {
+    Carver c(ws);
+    c.off = compute_bytes(s);
+    const size_t row_bytes = (size_t)s.d * (s.dtype == MEFT_BF16 ? 2 : 4);
+    Kd = c.take<char>((size_t)s.N * row_bytes);
+    Vd = c.take<char>((size_t)s.N * row_bytes);
+    dKd = c.take<char>((size_t)s.N * row_bytes);
+    dVd = c.take<char>((size_t)s.N * row_bytes);
+    pair_blk = c.take<int32_t>((size_t)s.T * s.top_k);
+    pair_blk_cnt = c.take<int32_t>(s.n_blocks);
+    bytes = c.off;
+  }
+};
+
+size_t workspace_bytes(const meft_shape& s) {
+  return (s.flags & MEFT_FLAG_HOST_KV) ? HostKvWs(s, nullptr).bytes : compute_bytes(s);
+}
+
+// ---- host-resident keys/values: side stream, events, pinned read-back buffer (created on first use) ----
+struct HostKvState {
+  hipStream_t side = nullptr;
+  hipEvent_t ev_entry = nullptr, ev_cnt = nullptr, ev_k = nullptr, ev_v = nullptr;
+  int32_t* host_cnt = nullptr;
+  bool ready = false;
+};
+HostKvState g_hkv;
+
+bool hostkv_init() {
+  if (g_hkv.ready) return true;
+  if (hipStreamCreateWithFlags(&g_hkv.side, hipStreamNonBlocking) != hipSuccess) return false;
+  hipEvent_t* evs[4] = {&g_hkv.ev_entry, &g_hkv.ev_cnt, &g_hkv.ev_k, &g_hkv.ev_v};
+  for (hipEvent_t* e : evs)
+    if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return false;
+  if (hipHostMalloc(reinterpret_cast<void**>(&g_hkv.host_cnt), (size_t)kMaxBlocks * sizeof(int32_t), hipHostMallocDefault) !=
+      hipSuccess)
+    return false;
+  g_hkv.ready = true;
+  return true;
+}
+
+// Reads the per-block entry counts back (the host blocks until the work queued on `st` so far has produced them),
+// then copies the blocks that some token uses from the pinned host matrices to their device copies on the side
+// stream: `first` before `second`, each followed by its event.
+meft_status hostkv_fetch(const meft_shape& s, const int32_t* cnt_dev, const void* first_host, char* first_dev,
+                         hipEvent_t first_ev, const void* second_host, char* second_dev, hipEvent_t second_ev,
+                         hipStream_t st) {
+  HostKvState& k = g_hkv;
+  if (hipMemcpyAsync(k.host_cnt, cnt_dev, (size_t)s.n_blocks * sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+    return MEFT_ERR_DEVICE;
+  if (hipEventRecord(k.ev_cnt, st) != hipSuccess || hipEventSynchronize(k.ev_cnt) != hipSuccess) return MEFT_ERR_DEVICE;
+  const size_t block_bytes = (size_t)s.block_size * s.d * (s.dtype == MEFT_BF16 ? 2 : 4);
+  const void* host[2] = {first_host, second_host};
+  char* dev[2] = {first_dev, second_dev};
+  hipEvent_t ev[2] = {first_ev, second_ev};
+  for (int m = 0; m < 2; ++m) {
+    for (int b = 0; b < s.n_blocks; ++b) {
+      if (k.host_cnt[b] <= 0) continue;
+      if (hipMemcpyAsync(dev[m] + (size_t)b * block_bytes, static_cast<const char*>(host[m]) + (size_t)b * block_bytes,
+                         block_bytes, hipMemcpyHostToDevice, k.side) != hipSuccess)
+        return MEFT_ERR_DEVICE;
+    }
+    if (hipEventRecord(ev[m], k.side) != hipSuccess) return MEFT_ERR_DEVICE;
+  }
+  return MEFT_OK;
 }
 
 // every entry point asks for the same size, the one meft_workspace_bytes() reports
@@ -296,6 +366,128 @@ void launch_reduce_parts(const meft_shape& s, const uint16_t* part, const Dispat
 
 using namespace meft;
 
+// Forward on device-resident K, V.  wait_k / wait_v (may be null): events the stream must wait for before
+// the first kernel that reads K / V (used when they are being staged from host memory).
+static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, const void* V,
+                            const int32_t* block_idx, void* out, int32_t* idx, float* act, const FwdWs& w,
+                            hipStream_t st, hipEvent_t wait_k, hipEvent_t wait_v) {
+  const int n_ent = s.T * s.top_e;
+  const int C = s.top_e * s.block_size;
+  const int BM = s.dtype == MEFT_BF16 ? kGemmBM : kGemmF32BM;
+
+  const bool dense = use_dense(s);
+  MEFT_LAUNCH("sort_blocks", sort_blocks_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, block_idx, s.T,
+              s.top_e, s.n_blocks, w.sblk);
+  launch_dispatch(s, w, BM, dense, st);
+  const int bsp = round64(s.block_size);
+  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
+  const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
+                 *vv = static_cast<const uint16_t*>(V);
+  if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+  if (dense) {
+    ProbTokKC<false> ps{};
+    ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
+    ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
+    launch_gemm_mfma("score_gemm", ps, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
+  } else {
+    GemmNTArgs a{};
+    a.A = h; a.Bm = K; a.C = w.sc; a.perm = w.perm; a.group_off = w.group_off; a.tile_off = w.tile_off;
+    a.n_groups = s.n_blocks; a.M = 0; a.Ng = s.block_size; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d;
+    a.ldc = s.block_size; a.e = s.top_e;
+    // upper bound on the number of m-tiles: every group may end with one partial tile
+    const int nb_used = s.n_blocks < n_ent ? s.n_blocks : n_ent;
+    launch_gemm_nt(s, a, n_ent / kGemmBM + nb_used, n_ent / kGemmF32BM + nb_used, "score_gemm", st);
+  }
+  MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
+              s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
+  if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+  if (dense) {
+    ProbTokNC pv{};
+    pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
+    pv.d = s.d; pv.part = w.part;
+    launch_gemm_mfma("value_gemm", pv, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
+    launch_reduce_parts(s, w.part, w, out, st);
+  } else if (s.dtype == MEFT_BF16) {
+    launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
+  } else {
+    launch_gather_fwd<float>(s, V, idx, act, out, st);
+  }
+  return launch_status();
+}
+
+// Backward on device-resident K, V, dK, dV.  wait_v / wait_k as in fwd_impl.
+static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, const void* V, const int32_t* idx,
+                            const float* act, const void* dOut, void* dh, void* dK, void* dV, int32_t* touched,
+                            int32_t* n_touched, const BwdWs& w, hipStream_t st, hipEvent_t wait_k,
+                            hipEvent_t wait_v) {
+  const int P = s.T * s.top_k;
+
+  if (use_dense(s)) {
+    const int n_ent = s.T * s.top_e;
+    const int bsp = round64(s.block_size);
+    const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
+                   *vv = static_cast<const uint16_t*>(V), *gg = static_cast<const uint16_t*>(dOut);
+    MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
+                st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
+    launch_dispatch(s, w, kGemmBM, true, st);
+    // flag, A', A'^T start from zero (flag..ApT are adjacent in the workspace); 4-byte fill
+    const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.DS) - reinterpret_cast<char*>(w.flag)) / 4;
+    MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
+                clear_words, 0);
+    MEFT_LAUNCH("scatter_act", scatter_act_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, act, P, s.top_k,
+                s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.group_off, w.goffp, w.Ap, w.ApT, w.flag);
+    const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
+    MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
+    MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
+                touched, n_touched);
+    const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
+    if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+    ProbTokKC<true> pg{};
+    pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
+    pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
+    launch_gemm_mfma("dact_gemm", pg, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
+    if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+    if (dh) {
+      ProbTokNC ph{};
+      ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
+      ph.d = s.d; ph.part = w.part;
+      launch_gemm_mfma("dh_gemm", ph, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
+      launch_reduce_parts(s, w.part, w, dh, st);
+    }
+    const int neu_grid = kXcd * ((s.n_blocks + kXcd - 1) / kXcd) * ((s.block_size + kTM - 1) / kTM) *
+                         ((s.d + kTN - 1) / kTN);
+    ProbNeuNC pn{};
+    pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
+    pn.n_groups = s.n_blocks; pn.bs = s.block_size; pn.d = s.d;
+    pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
+    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
+    pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
+    launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
+    (void)n_ent;
+    return launch_status();
+  }
+
+  if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+  if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+  if (s.dtype == MEFT_BF16) launch_gather_bwd<bf16_t>(s, K, V, dOut, idx, act, w.ds, dh, st);
+  else launch_gather_bwd<float>(s, K, V, dOut, idx, act, w.ds, dh, st);
+
+  const size_t n_clear = (size_t)(w.cursor - w.cnt_n) + s.N;  // cnt, its padding, cursor
+  MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((n_clear + 255) / 256)), dim3(256), 0, st, w.cnt_n,
+              n_clear, 0);
+  MEFT_LAUNCH("pair_count", pair_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.cnt_n);
+  MEFT_LAUNCH("pair_scan", pair_scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt_n, s.N, w.seg_off, touched,
+              n_touched);
+  MEFT_LAUNCH("pair_fill", pair_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.seg_off,
+              w.cursor, w.pair_list);
+  const int n_seg = s.N < P ? s.N : P;  // upper bound on the number of touched neurons
+  MEFT_LAUNCH("seg_sort", seg_sort_kernel, dim3(n_seg), dim3(256), 0, st, touched, n_touched, w.seg_off,
+              w.pair_list, w.pair_sorted);
+  if (s.dtype == MEFT_BF16) launch_seg_reduce<bf16_t>(s, w, touched, n_touched, act, h, dOut, dK, dV, n_seg, st);
+  else launch_seg_reduce<float>(s, w, touched, n_touched, act, h, dOut, dK, dV, n_seg, st);
+  return launch_status();
+}
+
 extern "C" {
 
 meft_status meft_check_shape(const meft_shape* shape) { return check_shape(shape); }
@@ -358,46 +550,19 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int n_ent = s.T * s.top_e;
-  const int C = s.top_e * s.block_size;
-  const int BM = s.dtype == MEFT_BF16 ? kGemmBM : kGemmF32BM;
+  if (!(s.flags & MEFT_FLAG_HOST_KV)) return fwd_impl(s, h, K, V, block_idx, out, idx, act, w, st, nullptr, nullptr);
 
-  const bool dense = use_dense(s);
+  // K, V in pinned host memory: find the blocks in use, fetch them on the side stream (K first, then V) while
+  // the dispatch runs, and let the scoring wait for K and the value stage for V.
+  if (!hostkv_init()) return MEFT_ERR_DEVICE;
+  HostKvWs hw(s, ws);
+  if (hipEventRecord(g_hkv.ev_entry, st) != hipSuccess || hipStreamWaitEvent(g_hkv.side, g_hkv.ev_entry, 0) != hipSuccess)
+    return MEFT_ERR_DEVICE;   // the device copies may still be read by work queued earlier on this stream
   MEFT_LAUNCH("sort_blocks", sort_blocks_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, block_idx, s.T,
               s.top_e, s.n_blocks, w.sblk);
-  launch_dispatch(s, w, BM, dense, st);
-  const int bsp = round64(s.block_size);
-  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
-  const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
-                 *vv = static_cast<const uint16_t*>(V);
-  if (dense) {
-    ProbTokKC<false> ps{};
-    ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
-    ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
-    launch_gemm_mfma("score_gemm", ps, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
-  } else {
-    GemmNTArgs a{};
-    a.A = h; a.Bm = K; a.C = w.sc; a.perm = w.perm; a.group_off = w.group_off; a.tile_off = w.tile_off;
-    a.n_groups = s.n_blocks; a.M = 0; a.Ng = s.block_size; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d;
-    a.ldc = s.block_size; a.e = s.top_e;
-    // upper bound on the number of m-tiles: every group may end with one partial tile
-    const int nb_used = s.n_blocks < n_ent ? s.n_blocks : n_ent;
-    launch_gemm_nt(s, a, n_ent / kGemmBM + nb_used, n_ent / kGemmF32BM + nb_used, "score_gemm", st);
-  }
-  MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
-              s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
-  if (dense) {
-    ProbTokNC pv{};
-    pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
-    pv.d = s.d; pv.part = w.part;
-    launch_gemm_mfma("value_gemm", pv, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
-    launch_reduce_parts(s, w.part, w, out, st);
-  } else if (s.dtype == MEFT_BF16) {
-    launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
-  } else {
-    launch_gather_fwd<float>(s, V, idx, act, out, st);
-  }
-  return launch_status();
+  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, s.T * s.top_e, w.cnt);
+  if ((rc = hostkv_fetch(s, w.cnt, K, hw.Kd, g_hkv.ev_k, V, hw.Vd, g_hkv.ev_v, st)) != MEFT_OK) return rc;
+  return fwd_impl(s, h, hw.Kd, hw.Vd, block_idx, out, idx, act, w, st, g_hkv.ev_k, g_hkv.ev_v);
 }
 
 meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* K, const void* V,
@@ -418,67 +583,31 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3(1), dim3(64), 0, st, n_touched, (size_t)1, 0);
     return launch_status();
   }
-  const int P = s.T * s.top_k;
+  if (!(s.flags & MEFT_FLAG_HOST_KV))
+    return bwd_impl(s, h, K, V, idx, act, dOut, dh, dK, dV, touched, n_touched, w, st, nullptr, nullptr);
 
-  if (use_dense(s)) {
-    const int n_ent = s.T * s.top_e;
-    const int bsp = round64(s.block_size);
-    const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
-                   *vv = static_cast<const uint16_t*>(V), *gg = static_cast<const uint16_t*>(dOut);
-    MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
-                st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
-    launch_dispatch(s, w, kGemmBM, true, st);
-    // flag, A', A'^T start from zero (flag..ApT are adjacent in the workspace); 4-byte fill
-    const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.DS) - reinterpret_cast<char*>(w.flag)) / 4;
-    MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
-                clear_words, 0);
-    MEFT_LAUNCH("scatter_act", scatter_act_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, act, P, s.top_k,
-                s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.group_off, w.goffp, w.Ap, w.ApT, w.flag);
-    const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
-    MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
-    MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
-                touched, n_touched);
-    const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
-    ProbTokKC<true> pg{};
-    pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
-    pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
-    launch_gemm_mfma("dact_gemm", pg, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
-    if (dh) {
-      ProbTokNC ph{};
-      ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
-      ph.d = s.d; ph.part = w.part;
-      launch_gemm_mfma("dh_gemm", ph, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
-      launch_reduce_parts(s, w.part, w, dh, st);
-    }
-    const int neu_grid = kXcd * ((s.n_blocks + kXcd - 1) / kXcd) * ((s.block_size + kTM - 1) / kTM) *
-                         ((s.d + kTN - 1) / kTN);
-    ProbNeuNC pn{};
-    pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
-    pn.n_groups = s.n_blocks; pn.bs = s.block_size; pn.d = s.d;
-    pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
-    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
-    pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
-    launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
-    (void)n_ent;
-    return launch_status();
-  }
-
-  if (s.dtype == MEFT_BF16) launch_gather_bwd<bf16_t>(s, K, V, dOut, idx, act, w.ds, dh, st);
-  else launch_gather_bwd<float>(s, K, V, dOut, idx, act, w.ds, dh, st);
-
-  const size_t n_clear = (size_t)(w.cursor - w.cnt_n) + s.N;  // cnt, its padding, cursor
-  MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((n_clear + 255) / 256)), dim3(256), 0, st, w.cnt_n,
-              n_clear, 0);
-  MEFT_LAUNCH("pair_count", pair_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.cnt_n);
-  MEFT_LAUNCH("pair_scan", pair_scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt_n, s.N, w.seg_off, touched,
-              n_touched);
-  MEFT_LAUNCH("pair_fill", pair_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.seg_off,
-              w.cursor, w.pair_list);
-  const int n_seg = s.N < P ? s.N : P;  // upper bound on the number of touched neurons
-  MEFT_LAUNCH("seg_sort", seg_sort_kernel, dim3(n_seg), dim3(256), 0, st, touched, n_touched, w.seg_off,
-              w.pair_list, w.pair_sorted);
-  if (s.dtype == MEFT_BF16) launch_seg_reduce<bf16_t>(s, w, touched, n_touched, act, h, dOut, dK, dV, n_seg, st);
-  else launch_seg_reduce<float>(s, w, touched, n_touched, act, h, dOut, dK, dV, n_seg, st);
+  // K, V, dK, dV in pinned host memory: fetch the blocks that hold a selected neuron (V first: the activation
+  // gradient needs it before dh needs K), compute into device staging, then write the touched rows back.
+  if (!hostkv_init()) return MEFT_ERR_DEVICE;
+  HostKvWs hw(s, ws);
+  if (hipEventRecord(g_hkv.ev_entry, st) != hipSuccess || hipStreamWaitEvent(g_hkv.side, g_hkv.ev_entry, 0) != hipSuccess)
+    return MEFT_ERR_DEVICE;
+  int32_t* sblk_tmp = hw.pair_blk;
+  int32_t* cnt_tmp = hw.pair_blk_cnt;
+  MEFT_LAUNCH("blocks_of_pairs", blocks_of_pairs_kernel, dim3((s.T * s.top_k + 255) / 256), dim3(256), 0, st, idx,
+              s.T * s.top_k, s.N, s.block_size, sblk_tmp);
+  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(1024), 0, st, sblk_tmp, s.T * s.top_k,
+              cnt_tmp);
+  if ((rc = hostkv_fetch(s, cnt_tmp, V, hw.Vd, g_hkv.ev_v, K, hw.Kd, g_hkv.ev_k, st)) != MEFT_OK) return rc;
+  rc = bwd_impl(s, h, hw.Kd, hw.Vd, idx, act, dOut, dh, hw.dKd, hw.dVd, touched, n_touched, w, st, g_hkv.ev_k,
+                g_hkv.ev_v);
+  if (rc != MEFT_OK) return rc;
+  const int n_rows = s.N < s.T * s.top_k ? s.N : s.T * s.top_k;
+  const int vec = s.d * (s.dtype == MEFT_BF16 ? 2 : 4) / 16;
+  MEFT_LAUNCH("rows_to_host", rows_to_host_kernel, dim3(n_rows), dim3(256), 0, st, touched, n_touched,
+              reinterpret_cast<const u32x4*>(hw.dVd), reinterpret_cast<u32x4*>(dV), vec);
+  MEFT_LAUNCH("rows_to_host", rows_to_host_kernel, dim3(n_rows), dim3(256), 0, st, touched, n_touched,
+              reinterpret_cast<const u32x4*>(hw.dKd), reinterpret_cast<u32x4*>(dK), vec);
   return launch_status();
 }
 

@@ -20,6 +20,26 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4* __restrict__ dst
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// block id of every (token, neuron) pair (ids clamped into range)
+__global__ void blocks_of_pairs_kernel(const int32_t* __restrict__ idx, int P, int N, int bs,
+                                       int32_t* __restrict__ blk) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < P) blk[p] = clampi(idx[p], 0, N - 1) / bs;
+}
+
+// copies the rows listed in touched[0 .. *n_touched) from a device matrix to the same rows of a matrix in
+// pinned host memory (the device writes over the host link); one workgroup per listed row, `vec` 16-byte
+// words per row
+__global__ __launch_bounds__(256) void rows_to_host_kernel(const int32_t* __restrict__ touched,
+                                                           const int32_t* __restrict__ n_touched,
+                                                           const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                           int vec) {
+  const int u = blockIdx.x;
+  if (u >= *n_touched) return;
+  const size_t row = (size_t)touched[u] * vec;
+  for (int i = threadIdx.x; i < vec; i += 256) dst[row + i] = src[row + i];
+}
+
 // cnt[j] += 1 for every pair
 __global__ void pair_count_kernel(const int32_t* __restrict__ idx, int P, int N, int32_t* __restrict__ cnt) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;

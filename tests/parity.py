@@ -41,6 +41,14 @@ def to_device(t: synth.Tensors, name: str):
     return torch.from_numpy(a).cuda()
 
 
+def to_pinned(t: synth.Tensors, name: str):
+    torch = _torch()
+    a = t.storage(name)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).pin_memory()
+    return torch.from_numpy(a).pin_memory()
+
+
 def to_host(x) -> np.ndarray:
     torch = _torch()
     if x.dtype == torch.bfloat16:
@@ -58,10 +66,15 @@ class DeviceLayer:
         self.B = binding
         c = t.cfg
         self.cfg = c
-        self.shape = binding.make_shape(c.T, c.d, c.n_blocks, c.block_size, c.top_e, c.top_k, c.dtype)
+        self.shape = binding.make_shape(c.T, c.d, c.n_blocks, c.block_size, c.top_e, c.top_k, c.dtype,
+                                        flags=binding.MEFT_FLAG_HOST_KV if c.host_kv else 0)
         self.dt = torch.bfloat16 if c.dtype == "bf16" else torch.float32
         dev = "cuda"
-        self.h, self.Wg, self.K, self.V, self.dOut = (to_device(t, n) for n in ("h", "Wg", "K", "V", "dOut"))
+        self.h, self.Wg, self.dOut = (to_device(t, n) for n in ("h", "Wg", "dOut"))
+        if c.host_kv:   # keys and values (and their gradients) stay in pinned host memory
+            self.K, self.V = (to_pinned(t, n) for n in ("K", "V"))
+        else:
+            self.K, self.V = (to_device(t, n) for n in ("K", "V"))
         self.bias = None if t.bias is None else torch.from_numpy(t.bias).cuda()
         T, d, N, e, k = c.T, c.d, c.N, c.top_e, c.top_k
         self.block_idx = torch.full((T, e), -1, dtype=torch.int32, device=dev)
@@ -70,8 +83,12 @@ class DeviceLayer:
         self.idx = torch.full((T, k), -1, dtype=torch.int32, device=dev)
         self.act = torch.zeros((T, k), dtype=torch.float32, device=dev)
         self.dh = torch.zeros((T, d), dtype=self.dt, device=dev)
-        self.dK = torch.zeros((N, d), dtype=self.dt, device=dev)
-        self.dV = torch.zeros((N, d), dtype=self.dt, device=dev)
+        if c.host_kv:
+            self.dK = torch.zeros((N, d), dtype=self.dt).pin_memory()
+            self.dV = torch.zeros((N, d), dtype=self.dt).pin_memory()
+        else:
+            self.dK = torch.zeros((N, d), dtype=self.dt, device=dev)
+            self.dV = torch.zeros((N, d), dtype=self.dt, device=dev)
         self.touched = torch.full((max(1, min(N, T * k)),), -1, dtype=torch.int32, device=dev)
         self.n_touched = torch.full((1,), -1, dtype=torch.int32, device=dev)
         nbytes = binding.meft_workspace_bytes(self.shape)
@@ -126,7 +143,7 @@ class DeviceLayer:
                 r[name] = to_host(x)
                 r[name + "_bits"] = x.view(ibits).cpu().numpy()
             else:
-                sel = torch.from_numpy(np.asarray(rows, np.int64)).cuda()
+                sel = torch.from_numpy(np.asarray(rows, np.int64)).to(x.device)
                 r[name] = to_host(x.index_select(0, sel))
         r["grad_rows"] = None if rows is None else np.asarray(rows, np.int64)
         return r

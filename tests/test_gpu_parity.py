@@ -96,6 +96,29 @@ def test_degenerate_selections(P, dtype):
     _case(P, T=40, d=8, n_blocks=48, block_size=1, top_e=6, top_k=6, dtype=dtype, seed=206)     # one neuron per expert
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 72)])
+def test_keys_and_values_in_pinned_host_memory(P, dtype, d):
+    """MEFT_FLAG_HOST_KV: K, V are read from, and the touched rows of dK, dV written to, pinned host memory.
+    Same kernels as the device-resident path, so the results must be bit-identical to it; block 3 is never
+    routed to, so its rows are neither fetched nor written."""
+    cfg = synth.small_case(T=150, d=d, n_blocks=6, block_size=32, top_e=2, top_k=12, dtype=dtype, seed=801)
+    t = synth.make_inputs(cfg)
+    t.bias = np.array([0, 0, 0, -100, 0, 0], np.float32)
+    ref = P.run_gpu(t)
+    th = synth.Tensors(cfg.replace(host_kv=True), t.h, t.Wg, t.K, t.V, t.dOut, t.bias, t.outlier_channels)
+    got = P.run_gpu(th)
+    for n in ("block_idx", "idx", "act", "out", "dh", "dK_bits", "dV_bits", "touched"):
+        assert (ref[n] == got[n]).all(), n
+    assert not ((got["touched"] >= 96) & (got["touched"] < 128)).any()
+    from oracle import oracle
+    r = oracle.route(t.h, t.Wg, cfg.top_e, t.bias)
+    f = oracle.forward(t.h, t.K, t.V, r.block_idx, cfg.block_size, cfg.top_k, want_candidates=True)
+    b = oracle.backward(t.h, t.K, t.V, f.idx, f.score, t.dOut, cfg.block_size)
+    rep = P.compare(th, got, r, f, b)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+
+
 def test_dense_case_matches_numpy_dense_adapter(P):
     """top_e = n_blocks, top_k = N: the GPU result is the dense parallel adapter (Section 2)."""
     from oracle import dense_ref
