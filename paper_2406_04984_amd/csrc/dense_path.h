@@ -195,7 +195,8 @@ struct ProbNeuNC {
     tc.slot0 = group_off[tc.g];
     const int rows = group_off[tc.g + 1] - tc.slot0;
     if (rows == 0) return false;
-    tc.m0 = (w / tn) * kTM; tc.n0 = (w % tn) * kTN; tc.Mrows = bs; tc.Ncols = d; tc.nk = round_up64(rows) / kTK;
+    // m tiles vary fastest: the tiles that share the gathered rows of one n tile run together
+    tc.m0 = (w % tm) * kTM; tc.n0 = (w / tm) * kTN; tc.Mrows = bs; tc.Ncols = d; tc.nk = round_up64(rows) / kTK;
     tc.aux = rows;
     return true;
   }

@@ -246,36 +246,49 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p) {
 }
 
 // ---- tile schedule shared by the token-major problems ----------------------------------------
-// sched[x][i] = (group, m tile) pairs that XCD x works through, in order; sched_len[x] their number.
+// XCD x works through the groups g with g % 8 == x, in ascending order.  grp[x][i] = (group, number of
+// m tiles of the groups before it in this XCD's list); an end entry (-1, total m tiles) closes the list.
+// Inside a group the m tiles vary fastest, so that the tiles that share a B panel (one n tile of the
+// group's block) run at the same time and the panel is read from HBM once.
 struct TokenSched {
-  const int2* pairs;     // [kXcd][cap]
-  const int* len;        // [kXcd]
-  int cap;
+  const int2* grp;       // [kXcd][cap_groups + 1]
+  const int* len;        // [kXcd] number of groups in the list
+  int cap;               // entries per XCD (groups + 1)
+  int max_tiles;         // upper bound of m tiles per XCD (for the grid size)
 };
 
-// One thread per XCD lists the m tiles of its groups (groups g with g % 8 == x).
+// One thread per XCD lists its groups.
 __global__ void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups, int cap,
-                                   int2* __restrict__ pairs, int* __restrict__ len) {
+                                   int2* __restrict__ grp, int* __restrict__ len) {
   const int x = threadIdx.x;
   if (x >= kXcd) return;
-  int n = 0;
+  int n = 0, tiles = 0;
   for (int g = x; g < n_groups; g += kXcd) {
     const int rows = group_off[g + 1] - group_off[g];
-    const int tm = (rows + kTM - 1) / kTM;
-    for (int i = 0; i < tm && n < cap; ++i) pairs[(size_t)x * cap + n++] = make_int2(g, i);
+    if (rows == 0) continue;
+    grp[(size_t)x * cap + n++] = make_int2(g, tiles);
+    tiles += (rows + kTM - 1) / kTM;
   }
+  grp[(size_t)x * cap + n] = make_int2(-1, tiles);
   len[x] = n;
 }
 
 __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,
                                                    int& g, int& mt, int& nt, int& slot0, int& rows) {
   const int x = wg & (kXcd - 1), local = wg >> 3;
-  const int pi = local / tn;
-  if (pi >= s.len[x]) return false;
-  nt = local - pi * tn;
-  const int2 gm = s.pairs[(size_t)x * s.cap + pi];
-  g = gm.x;
-  mt = gm.y;
+  const int n = s.len[x];
+  const int2* list = s.grp + (size_t)x * s.cap;
+  if (local >= list[n].y * tn) return false;
+  int lo = 0, hi = n;  // list[lo].y * tn <= local < list[hi].y * tn
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (list[mid].y * tn <= local) lo = mid; else hi = mid;
+  }
+  g = list[lo].x;
+  const int tm = list[lo + 1].y - list[lo].y;
+  const int w = local - list[lo].y * tn;
+  nt = w / tm;
+  mt = w - nt * tm;
   slot0 = group_off[g];
   rows = group_off[g + 1] - slot0;
   return true;

@@ -95,7 +95,9 @@ bool use_dense(const meft_shape& s) {
 }
 
 int round64(int v) { return (v + 63) & ~63; }
-int sched_cap(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + (s.n_blocks + kXcd - 1) / kXcd + 1); }
+// per XCD: at most ceil(n_blocks/8) groups (+1 end entry) and this many m tiles
+int sched_cap(const meft_shape& s) { return (s.n_blocks + kXcd - 1) / kXcd + 1; }
+int sched_max_tiles(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + (s.n_blocks + kXcd - 1) / kXcd + 1); }
 
 constexpr int kRouterSplitMax = 4;
 
@@ -380,7 +382,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
               s.top_e, s.n_blocks, w.sblk);
   launch_dispatch(s, w, BM, dense, st);
   const int bsp = round64(s.block_size);
-  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
+  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
   const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
                  *vv = static_cast<const uint16_t*>(V);
   if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
@@ -388,7 +390,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokKC<false> ps{};
     ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
     ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
-    launch_gemm_mfma("score_gemm", ps, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
+    launch_gemm_mfma("score_gemm", ps, kXcd * sched.max_tiles * ((s.block_size + kTN - 1) / kTN), st);
   } else {
     GemmNTArgs a{};
     a.A = h; a.Bm = K; a.C = w.sc; a.perm = w.perm; a.group_off = w.group_off; a.tile_off = w.tile_off;
@@ -405,7 +407,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokNC pv{};
     pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
     pv.d = s.d; pv.part = w.part;
-    launch_gemm_mfma("value_gemm", pv, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
+    launch_gemm_mfma("value_gemm", pv, kXcd * sched.max_tiles * ((s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(s, w.part, w, out, st);
   } else if (s.dtype == MEFT_BF16) {
     launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
@@ -440,18 +442,18 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
     MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
                 touched, n_touched);
-    const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s)};
+    const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<true> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
     pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
-    launch_gemm_mfma("dact_gemm", pg, kXcd * sched.cap * ((s.block_size + kTN - 1) / kTN), st);
+    launch_gemm_mfma("dact_gemm", pg, kXcd * sched.max_tiles * ((s.block_size + kTN - 1) / kTN), st);
     if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     if (dh) {
       ProbTokNC ph{};
       ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
       ph.d = s.d; ph.part = w.part;
-      launch_gemm_mfma("dh_gemm", ph, kXcd * sched.cap * ((s.d + kTN - 1) / kTN), st);
+      launch_gemm_mfma("dh_gemm", ph, kXcd * sched.max_tiles * ((s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
     const int neu_grid = kXcd * ((s.n_blocks + kXcd - 1) / kXcd) * ((s.block_size + kTM - 1) / kTM) *
