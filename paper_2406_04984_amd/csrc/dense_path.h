@@ -43,12 +43,12 @@ struct ProbRouter {
   __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
     return Wg + (size_t)(n < B ? n : B - 1) * d + (size_t)tc.aux * tc.nk * kTK;
   }
-  __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+  __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
     float* dst = p + (size_t)tc.aux * T * B;
-    for (int idx = tid; idx < kTM * kTN; idx += 256) {
+    for (int idx = tid; idx < kEpiRows * kTN; idx += 256) {
       const int r = idx / kTN, c = idx - r * kTN;
-      const int m = tc.m0 + r, n = tc.n0 + c;
-      if (m < T && n < B) dst[(size_t)m * B + n] = tile[tile_index(r, c)];
+      const int m = tc.m0 + r0 + r, n = tc.n0 + c;
+      if (m < T && n < B) dst[(size_t)m * B + n] = rows[tile_index(r, c)];
     }
   }
 };
@@ -80,15 +80,20 @@ struct ProbTokKC {
   __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
     return W + ((size_t)tc.g * bs + (n < bs ? n : bs - 1)) * d;
   }
-  __device__ void store_tile(const TileCoord& tc, float* tile, int tid) const {
+  __device__ void store_rows(const TileCoord& tc, int r0, float* rows, int tid) const {
     if constexpr (!MASKED) {
-      // a wave stores one row per step: 64 lanes x 4 floats = the 256 columns of the tile
+      // a wave stores one row per step: 64 lanes x 4 floats = the 256 columns of the tile.  The row's entry id is
+      // wave-uniform and read through the constant address space (a scalar load).
+      const auto* cperm = as_const(perm);
       const int c = (tid & 63) * 4, n = tc.n0 + c;
-      for (int r = tid >> 6; r < kTM; r += 4) {
-        const int m = tc.m0 + r;
+      const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+#pragma unroll
+      for (int it = 0; it < kEpiRows / 4; ++it) {
+        const int r = w + it * 4;
+        const int m = tc.m0 + r0 + r;
         if (m >= tc.Mrows) break;
-        float* dst = sc + (size_t)perm[tc.slot0 + m] * bs + n;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
+        float* dst = sc + (size_t)cperm[tc.slot0 + m] * bs + n;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
         if ((bs & 3) == 0) {
           if (n < bs) *reinterpret_cast<f32x4*>(dst) = v;
         } else {
@@ -98,15 +103,17 @@ struct ProbTokKC {
         }
       }
     } else {
-      // pass 1, slot-major: rows of 8 columns; mask by A' > 0, store DS', keep the masked value in the tile
+      // step 1, slot-major: 8 columns per thread; mask by A' > 0, store DS', keep the masked value in LDS
       const int c = (tid & 31) * 8, n = tc.n0 + c;
-      for (int r = tid >> 5; r < kTM; r += 8) {
-        const int m = tc.m0 + r;
+#pragma unroll
+      for (int it = 0; it < kEpiRows / 8; ++it) {
+        const int r = (tid >> 5) + it * 8;
+        const int m = tc.m0 + r0 + r;
         const bool row_in = m < tc.Mrows;
         float x[8];
         {
-          const f32x4 a = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
-          const f32x4 b = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c + 4)]);
+          const f32x4 a = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
+          const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
           x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
         }
         u32x4 mk = {0u, 0u, 0u, 0u};
@@ -120,20 +127,21 @@ struct ProbTokKC {
         }
         if (row_in && n < bsp) Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(DS) + (size_t)(tc.slot0 + m) * bsp + n, x);
         f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
-        *reinterpret_cast<f32x4*>(&tile[tile_index(r, c)]) = a;
-        *reinterpret_cast<f32x4*>(&tile[tile_index(r, c + 4)]) = b;
+        *reinterpret_cast<f32x4*>(&rows[tile_index(r, c)]) = a;
+        *reinterpret_cast<f32x4*>(&rows[tile_index(r, c + 4)]) = b;
       }
       __syncthreads();
-      // pass 2, neuron-major: column n, 8 consecutive slots -> one 16-byte store into DS'^T
+      // step 2, neuron-major: column n, 8 consecutive slots -> one 16-byte store into DS'^T
       const int Mgp = round_up64(tc.Mrows);
-      uint16_t* base = DST + (size_t)goffp[tc.g] * bs;
-      for (int idx = tid; idx < kTN * (kTM / 8); idx += 256) {
-        const int cc = idx & (kTN - 1), r8 = (idx >> 8) * 8;   // kTN == 256
-        const int nn = tc.n0 + cc, m = tc.m0 + r8;
+      uint16_t* base = DST + (size_t)as_const(goffp)[tc.g] * bs;
+#pragma unroll
+      for (int it = 0; it < kEpiRows / 8; ++it) {
+        const int cc = tid, r8 = it * 8;   // kTN == 256 == threads
+        const int nn = tc.n0 + cc, m = tc.m0 + r0 + r8;
         if (nn >= bs || m >= Mgp) continue;
         float x[8];
 #pragma unroll
-        for (int z = 0; z < 8; ++z) x[z] = tile[tile_index(r8 + z, cc)];
+        for (int z = 0; z < 8; ++z) x[z] = rows[tile_index(r8 + z, cc)];
         Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(base) + (size_t)nn * Mgp + m, x);
       }
     }
@@ -159,17 +167,18 @@ struct ProbTokNC {
   __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
     return A + (size_t)(tc.slot0 + (m < tc.Mrows ? m : tc.Mrows - 1)) * bsp;
   }
-  __device__ const uint16_t* b_row(const TileCoord& tc, int k) const {
-    return W + ((size_t)tc.g * bs + (k < bs ? k : bs - 1)) * d;
-  }
-  __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+  __device__ int b_row_id(const TileCoord& tc, int k) const { return tc.g * bs + (k < bs ? k : bs - 1); }
+  __device__ const uint16_t* b_row_ptr(int row) const { return W + (size_t)row * d; }
+  __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
     const int c = (tid & 31) * 8, n = tc.n0 + c;
     if (n >= d) return;   // d % 64 == 0: a group of 8 columns is fully in or out
-    for (int r = tid >> 5; r < kTM; r += 8) {
-      const int m = tc.m0 + r;
+#pragma unroll
+    for (int it = 0; it < kEpiRows / 8; ++it) {
+      const int r = (tid >> 5) + it * 8;
+      const int m = tc.m0 + r0 + r;
       if (m >= tc.Mrows) break;
-      const f32x4 a = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
-      const f32x4 b = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c + 4)]);
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
       const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
       Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(part) + (size_t)(tc.slot0 + m) * d + n, x);
     }
@@ -192,8 +201,8 @@ struct ProbNeuNC {
     const int gi = local / (tm * tn), w = local - gi * (tm * tn);
     tc.g = x + kXcd * gi;
     if (tc.g >= n_groups) return false;
-    tc.slot0 = group_off[tc.g];
-    const int rows = group_off[tc.g + 1] - tc.slot0;
+    tc.slot0 = as_const(group_off)[tc.g];
+    const int rows = as_const(group_off)[tc.g + 1] - tc.slot0;
     if (rows == 0) return false;
     // m tiles vary fastest: the tiles that share the gathered rows of one n tile run together
     tc.m0 = (w % tm) * kTM; tc.n0 = (w / tm) * kTN; tc.Mrows = bs; tc.Ncols = d; tc.nk = round_up64(rows) / kTK;
@@ -201,27 +210,33 @@ struct ProbNeuNC {
     return true;
   }
   __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
-    return AT + (size_t)goffp[tc.g] * bs + (size_t)(m < bs ? m : bs - 1) * round_up64(tc.aux);
+    return AT + (size_t)as_const(goffp)[tc.g] * bs + (size_t)(m < bs ? m : bs - 1) * round_up64(tc.aux);
   }
-  __device__ const uint16_t* b_row(const TileCoord& tc, int k) const {
-    // k is wave-uniform here; reading through the constant address space makes this a scalar load, which
-    // is counted apart from the vector loads that pace the operand pipeline
-    const auto* tos = reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(
-        reinterpret_cast<uintptr_t>(tok_of_slot));
-    return X + (size_t)tos[tc.slot0 + (k < tc.aux ? k : tc.aux - 1)] * d;
+  __device__ int b_row_id(const TileCoord& tc, int k) const {   // k is wave-uniform: a scalar load
+    return as_const(tok_of_slot)[tc.slot0 + (k < tc.aux ? k : tc.aux - 1)];
   }
-  __device__ void store_tile(const TileCoord& tc, const float* tile, int tid) const {
+  __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }
+  __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
+    // a wave stores two rows per step (32 lanes x 8 columns each); their touched flags are wave-uniform and
+    // read through the constant address space (scalar loads)
+    const auto* cflag = as_const(flag);
     const int c = (tid & 31) * 8, n = tc.n0 + c;
-    if (n >= d) return;   // d % 64 == 0: a group of 8 columns is fully in or out
-    for (int r = tid >> 5; r < kTM; r += 8) {
-      const int m = tc.m0 + r;
-      if (m >= bs) break;
-      const size_t j = (size_t)tc.g * bs + m;
-      if (flag[j] <= 0) continue;
-      const f32x4 a = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c)]);
-      const f32x4 b = *reinterpret_cast<const f32x4*>(&tile[tile_index(r, c + 4)]);
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hi = (tid >> 5) & 1;
+#pragma unroll
+    for (int it = 0; it < kEpiRows / 8; ++it) {
+      const int re = 2 * w + it * 8;                  // even row of this wave's pair
+      const int me = tc.m0 + r0 + re;
+      if (me >= bs) break;
+      const size_t je = (size_t)tc.g * bs + me;
+      const int f0 = cflag[je];
+      const int f1 = (me + 1 < bs) ? cflag[je + 1] : 0;
+      const int r = re + hi;
+      if ((hi ? f1 : f0) <= 0 || n >= d) continue;
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
       const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-      Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(G) + j * d + n, x);
+      Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(G) + (je + hi) * d + n, x);
     }
   }
 };

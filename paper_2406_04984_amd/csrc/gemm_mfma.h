@@ -37,6 +37,14 @@ constexpr int kXcd = 8;
 
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 
+// Read-only index arrays are read through the constant address space where the index is wave-uniform: that
+// makes the load a scalar load, which is counted apart from the vector loads that pace the operand pipeline
+// (a vector load would make the compiler wait for every outstanding operand load before using its result).
+template <typename T>
+__device__ __forceinline__ const __attribute__((address_space(4))) T* as_const(const T* p) {
+  return reinterpret_cast<const __attribute__((address_space(4))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+
 struct TileCoord {
   int g;       // group (block of neurons); 0 for an ungrouped problem
   int m0, n0;  // first row / column of the tile inside the group's problem
@@ -51,16 +59,20 @@ struct TileCoord {
 //   static constexpr bool kBNC;                         B contiguous along n?
 //   __device__ bool locate(int wg, TileCoord&) const;   false: no tile for this workgroup
 //   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
-//   __device__ const uint16_t* b_row(const TileCoord&, int r) const;   KC: row n; NC: row k (clamped)
-//   __device__ void store_tile(const TileCoord&, float* tile, int tid) const;   write the finished tile (in LDS)
+//   KC: __device__ const uint16_t* b_row(const TileCoord&, int n) const;   start of B row n (clamped)
+//   NC: __device__ int b_row_id(const TileCoord&, int k) const;  number of the row that holds k (clamped), and
+//       __device__ const uint16_t* b_row_ptr(int row) const;      its start
+//   __device__ void store_rows(const TileCoord&, int r0, float* rows, int tid) const;   write tile rows r0..r0+31
 //
 // acc[i][j][r] of a wave holds C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,
-// n = wn + j*32 + lane%32 (tile-local); the kernel lays the tile out row-major in LDS (tile_index) and hands
-// it to store_tile, which all 256 threads of the workgroup execute.
+// n = wn + j*32 + lane%32 (tile-local); the kernel lays 32 rows at a time out row-major in LDS (tile_index with
+// the row counted from the pass start) and hands them to store_rows, which all 256 threads execute.  Global
+// loads inside store_rows make the compiler wait for every outstanding vector-memory operation, including
+// the next tile's operand loads; policies therefore read per-row indices with scalar loads where they can.
 
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-// index of element (m, n) of the fp32 epilogue tile in LDS (see the epilogue of gemm_mfma_kernel)
+// index of element (m, n) of an epilogue pass in LDS, m counted from the first row of the pass
 __device__ __forceinline__ int tile_index(int m, int n) { return m * kTN + (n ^ (((m >> 2) & 1) << 7)); }
 
 // Eight transposing LDS reads (the four n-contiguous B fragments of one k16 step, low and high k half)
@@ -86,64 +98,77 @@ __device__ __forceinline__ void tr_read8(u32x2 (&o)[8], const uint32_t (&alo)[4]
       : "memory");
 }
 
+constexpr int kEpiRows = 32;   // rows of the output tile staged through LDS per epilogue pass
+
 template <class P>
-__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p) {
+__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  TileCoord tc;
-  if (!p.locate(blockIdx.x, tc)) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int LA = kTM / 8 / 4;                    // A wave-loads (8 rows x 128 B) per wave and stage: 4
   constexpr int LB = 8;                              // B wave-loads per wave and stage (KC: 8 rows x 128 B; NC: 2 rows x 512 B)
 
-  // ---- global -> LDS addressing ----
+  // The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ... (gridDim.x is a multiple of 8,
+  // so it stays on one XCD's list).  The first two operand stages of the next tile are requested before the
+  // epilogue of the current one, which hides the fill of the pipeline behind the output stores.
+  struct Loads {
+    const uint16_t* pa[LA];
+    const uint16_t* pb[LB];   // KC: fixed row pointers, advanced by k.  NC: unused (rows change with k)
+  };
   const int lr8 = lane >> 3;
-  const uint16_t* pa[LA];
+  auto next_tile = [&](int& wg, TileCoord& t) -> bool {
+    for (; wg < n_tiles_bound; wg += gridDim.x)
+      if (p.locate(wg, t)) return true;
+    return false;
+  };
+  auto setup = [&](Loads& L, const TileCoord& t) {
 #pragma unroll
-  for (int i = 0; i < LA; ++i) {
-    const int row = (wave * LA + i) * 8 + lr8;
-    pa[i] = p.a_row(tc, tc.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
-  }
-  const uint16_t* pb[LB];  // KC: fixed row pointers, advanced by k.  NC: recomputed per k tile.
-  int nc_col = 0;          // NC: element offset of this lane's chunk inside a B row (without swizzle)
-  if constexpr (!P::kBNC) {
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int row = (wave * LB + i) * 8 + lr8;
-      pb[i] = p.b_row(tc, tc.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+    for (int i = 0; i < LA; ++i) {
+      const int row = (wave * LA + i) * 8 + lr8;
+      L.pa[i] = p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
     }
-  } else {
-    nc_col = tc.n0;
-  }
-  auto issue = [&](int kt, int stage) {
+    if constexpr (!P::kBNC) {
+#pragma unroll
+      for (int i = 0; i < LB; ++i) {
+        const int row = (wave * LB + i) * 8 + lr8;
+        L.pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+      }
+    }
+  };
+  // NC: the wave's 16 B-row pointers of one k tile.  They are wave-uniform, so any index look-up behind them is a
+  // scalar load (it does not disturb the vector-memory counter that paces the pipeline).  They are fetched one
+  // k tile ahead of their use so that the wait for them is free.
+  struct Rows { int r[2 * LB]; };   // row numbers (32 bits each keep them in scalar registers)
+  auto rows_for = [&](Rows& R, const TileCoord& t, int kt) {
+    if constexpr (P::kBNC) {
+#pragma unroll
+      for (int z = 0; z < 2 * LB; ++z) R.r[z] = p.b_row_id(t, kt * kTK + wave * 2 * LB + z);
+    }
+  };
+  auto issue = [&](const Loads& L, const TileCoord& t, int kt, int stage, const Rows& R) {
     uint16_t* sa = smem + stage * kStageElems;
     uint16_t* sb = sa + kTM * kTK;
 #pragma unroll
     for (int i = 0; i < LA; ++i)
-      __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + kt * kTK), MEFT_LPTR(sa + (wave * LA + i) * 8 * kTK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pa[i] + kt * kTK), MEFT_LPTR(sa + (wave * LA + i) * 8 * kTK), 16, 0, 0);
     if constexpr (!P::kBNC) {
 #pragma unroll
       for (int i = 0; i < LB; ++i)
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(pb[i] + kt * kTK), MEFT_LPTR(sb + (wave * LB + i) * 8 * kTK), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pb[i] + kt * kTK), MEFT_LPTR(sb + (wave * LB + i) * 8 * kTK), 16, 0, 0);
     } else {
 #pragma unroll
       for (int i = 0; i < LB; ++i) {
-        const int kev = 2 * (wave * LB + i);                          // even k row of this wave-load (wave-uniform)
-        const int krow = kev + (lane >> 5);                           // this lane's k row inside the tile
+        const int krow = 2 * (wave * LB + i) + (lane >> 5);           // this lane's k row inside the tile
         const int chunk = (lane & 31) ^ (2 * (krow & 7));             // logical 16-byte chunk this lane fetches
-        int col = nc_col + chunk * 8;
-        col = col > tc.Ncols - 8 ? tc.Ncols - 8 : col;                // clamp (columns beyond Ncols are never stored)
-        // both row pointers are wave-uniform, so any index look-up behind them is a scalar load and
-        // does not disturb the vector-memory counter that paces the pipeline
-        const uint16_t* r0 = p.b_row(tc, kt * kTK + kev);
-        const uint16_t* r1 = p.b_row(tc, kt * kTK + kev + 1);
-        const uint16_t* src = ((lane >> 5) ? r1 : r0) + col;
+        int col = t.n0 + chunk * 8;
+        col = col > t.Ncols - 8 ? t.Ncols - 8 : col;                  // clamp (columns beyond Ncols are never stored)
+        const uint16_t* src = p.b_row_ptr((lane >> 5) ? R.r[2 * i + 1] : R.r[2 * i]) + col;
         __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (wave * LB + i) * 512), 16, 0, 0);
       }
     }
   };
 
-  // ---- fragment addressing ----
+  // ---- fragment addressing (the same for every tile) ----
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
   const int fr = lane & 31, fc = lane >> 5;
   int offA[2], keyA[2];
@@ -167,82 +192,123 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p) {
     }
   }
 
-  f32x16 acc[2][4];
+  int wg = blockIdx.x;
+  TileCoord tc;
+  if (!next_tile(wg, tc)) return;
+  Loads cur;
+  setup(cur, tc);
+  Rows rows;   // row pointers for the next k tile to be requested
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int s = 0; s < kStages - 1; ++s) {
+    rows_for(rows, tc, s);
+    if (s < tc.nk) issue(cur, tc, s, s, rows);
+  }
+  rows_for(rows, tc, kStages - 1);
 
-  const int nk = tc.nk;
+  for (;;) {
+    f32x16 acc[2][4];
 #pragma unroll
-  for (int s = 0; s < kStages - 1; ++s)
-    if (s < nk) issue(s, s);
-  int stage = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    // tile kt has landed once at most the loads of one later tile are still outstanding
-    if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    if (kt + kStages - 1 < nk) {
-      int ps = stage - 1;
-      if (ps < 0) ps += kStages;
-      issue(kt + kStages - 1, ps);  // the buffer of tile kt-1: every wave is past it (barrier above)
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = tc.nk;
+    int stage = 0;
+    bool more = false;
+    TileCoord tn;
+    Loads nxt;
+    for (int kt = 0; kt < nk; ++kt) {
+      // k tile kt has landed once at most LA + LB younger vector-memory operations are outstanding: the counter
+      // retires loads and stores in issue order (the compiler relies on the same), and everything issued after
+      // k tile kt's loads -- the next k tile's loads, or at kt == 0 also the previous output tile's stores --
+      // is younger.  With a single k tile nothing younger is guaranteed to exist, so everything is awaited.
+      if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+      if (kt + kStages - 1 < nk) {
+        int ps = stage - 1;
+        if (ps < 0) ps += kStages;
+        issue(cur, tc, kt + kStages - 1, ps, rows);  // the buffer of k tile kt-1: every wave is past it (barrier above)
+        rows_for(rows, tc, kt + kStages);                // pointers for the request of the next iteration
+      }
+      // The next tile is located early (scalar loads only) and its row pointers are set up during the last k
+      // tile, when no operand load is outstanding any more, so look-ups with vector loads cost no pipeline drain.
+      if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }
+      if (kt == nk - 1 && more) setup(nxt, tn);
+      const uint16_t* st = smem + stage * kStageElems;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 fa[2], fb[4];
+        const int c = ks * 2 + fc;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
+        if constexpr (!P::kBNC) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
+        } else {
+          // k16 step ks starts 16 rows = 8192 bytes further; that does not change (k & 7), so the swizzle holds
+          const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
+          uint32_t alo[4], ahi[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
+          u32x2 o[8];
+          if (ks == 0) tr_read8<0>(o, alo, ahi);
+          else if (ks == 1) tr_read8<8192>(o, alo, ahi);
+          else if (ks == 2) tr_read8<16384>(o, alo, ahi);
+          else tr_read8<24576>(o, alo, ahi);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
+            fb[j] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+      stage = stage + 1 == kStages ? 0 : stage + 1;
     }
-    const uint16_t* st = smem + stage * kStageElems;
+
+    // every wave is done reading operand stages; ask for the next tile's first stages (0 and 1) right away
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (more) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[2], fb[4];
-      const int c = ks * 2 + fc;
+      for (int s = 0; s < kStages - 1; ++s) {
+        rows_for(rows, tn, s);
+        if (s < tn.nk) issue(nxt, tn, s, s, rows);
+      }
+      rows_for(rows, tn, kStages - 1);
+    }
+
+    // ---- epilogue: the fp32 tile goes through the LDS region of stage 2, kEpiRows rows at a time, so that the
+    // policy can store whole rows with 16-byte accesses.  Layout of a pass: row-major, 256 floats per row, the
+    // two 128-float halves of a row swapped when (row >> 2) is odd (keeps the half-waves of one accumulator
+    // write in different banks).  Rows 32*pass .. +31 belong to the waves with wm == 64*(pass/2), fragment pass%2.
+    float* tile = reinterpret_cast<float*>(smem + (kStages - 1) * kStageElems);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
-      if constexpr (!P::kBNC) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
-      } else {
-        // k16 step ks starts 16 rows = 8192 bytes further; that does not change (k & 7), so the swizzle holds
-        const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
-        uint32_t alo[4], ahi[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
-        u32x2 o[8];
-        if (ks == 0) tr_read8<0>(o, alo, ahi);
-        else if (ks == 1) tr_read8<8192>(o, alo, ahi);
-        else if (ks == 2) tr_read8<16384>(o, alo, ahi);
-        else tr_read8<24576>(o, alo, ahi);
+    for (int pass = 0; pass < kTM / kEpiRows; ++pass) {
+      if ((wave >> 1) == (pass >> 1)) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
-          fb[j] = __builtin_bit_cast(bf16x8, w);
+          const int n = wn + j * 32 + fr;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int ml = (r >> 2) * 8 + fc * 4 + (r & 3);
+            tile[tile_index(ml, n)] = acc[pass & 1][j][r];
+          }
         }
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      p.store_rows(tc, pass * kEpiRows, tile, tid);
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
-    stage = stage + 1 == kStages ? 0 : stage + 1;
+    if (!more) break;
+    tc = tn;
+    cur = nxt;
   }
-
-  // ---- epilogue: the 128 x 256 fp32 tile goes through LDS so that the policy can store whole rows with
-  // 16-byte accesses.  Layout: row-major, 256 floats per row, the two 128-float halves of a row swapped
-  // when (row >> 2) is odd, which keeps the two half-waves of an accumulator write in different banks.
-  __syncthreads();  // every wave is done reading the last operand stage
-  float* tile = reinterpret_cast<float*>(smem);
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = wn + j * 32 + fr;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = wm + i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3);
-        tile[tile_index(m, n)] = acc[i][j][r];
-      }
-    }
-  __syncthreads();
-  p.store_tile(tc, tile, tid);
 }
 
 // ---- tile schedule shared by the token-major problems ----------------------------------------
@@ -276,8 +342,8 @@ __global__ void build_sched_kernel(const int32_t* __restrict__ group_off, int n_
 __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,
                                                    int& g, int& mt, int& nt, int& slot0, int& rows) {
   const int x = wg & (kXcd - 1), local = wg >> 3;
-  const int n = s.len[x];
-  const int2* list = s.grp + (size_t)x * s.cap;
+  const int n = as_const(s.len)[x];
+  const auto* list = as_const(s.grp) + (size_t)x * s.cap;
   if (local >= list[n].y * tn) return false;
   int lo = 0, hi = n;  // list[lo].y * tn <= local < list[hi].y * tn
   while (hi - lo > 1) {
@@ -289,8 +355,8 @@ __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int
   const int w = local - list[lo].y * tn;
   nt = w / tm;
   mt = w - nt * tm;
-  slot0 = group_off[g];
-  rows = group_off[g + 1] - slot0;
+  slot0 = as_const(group_off)[g];
+  rows = as_const(group_off)[g + 1] - slot0;
   return true;
 }
 

@@ -328,6 +328,8 @@ void launch_seg_reduce(const meft_shape& s, const BwdWs& w, const int32_t* touch
 }
 
 
+constexpr int kPersistentWgs = 256;   // compute units of an MI355X; a multiple of the 8 XCDs
+
 template <class P>
 void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st) {
   static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
@@ -336,7 +338,10 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
     configured = true;
   }
-  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(grid), dim3(256), kGemmLdsBytes, st, prob);
+  // persistent workgroups: one per compute unit (the LDS footprint allows no more), each walking the tile ids
+  // wg, wg + 256, ... below `grid`
+  const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
+  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(256), kGemmLdsBytes, st, prob, grid);
 }
 
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
