@@ -193,17 +193,17 @@ struct ProbNeuNC {
   const uint16_t* X;          // [T, d]
   const int32_t* group_off; const int32_t* goffp; const int32_t* tok_of_slot;
   const int32_t* flag;        // [N] > 0 where some token selected the neuron
-  int n_groups, bs, d;
+  TokenSched sched;           // only the group lists are used: every group has the same number of tiles
+  int bs, d;
   uint16_t* G;                // dV or dK [N, d]
   __device__ bool locate(int wg, TileCoord& tc) const {
     const int tm = (bs + kTM - 1) / kTM, tn = (d + kTN - 1) / kTN;
     const int x = wg & (kXcd - 1), local = wg >> 3;
     const int gi = local / (tm * tn), w = local - gi * (tm * tn);
-    tc.g = x + kXcd * gi;
-    if (tc.g >= n_groups) return false;
+    if (gi >= as_const(sched.len)[x]) return false;
+    tc.g = as_const(sched.grp)[(size_t)x * sched.cap + gi].x;
     tc.slot0 = as_const(group_off)[tc.g];
-    const int rows = as_const(group_off)[tc.g + 1] - tc.slot0;
-    if (rows == 0) return false;
+    const int rows = as_const(group_off)[tc.g + 1] - tc.slot0;   // > 0: the lists hold non-empty groups only
     // m tiles vary fastest: the tiles that share the gathered rows of one n tile run together
     tc.m0 = (w % tm) * kTM; tc.n0 = (w / tm) * kTN; tc.Mrows = bs; tc.Ncols = d; tc.nk = round_up64(rows) / kTK;
     tc.aux = rows;

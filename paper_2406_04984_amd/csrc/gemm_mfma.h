@@ -57,7 +57,8 @@ struct TileCoord {
 
 // A problem policy P provides:
 //   static constexpr bool kBNC;                         B contiguous along n?
-//   __device__ bool locate(int wg, TileCoord&) const;   false: no tile for this workgroup
+//   __device__ bool locate(int wg, TileCoord&) const;   false: no tile with id wg, nor with any larger id on
+//                                                       the same XCD (ids wg + 8, wg + 16, ...)
 //   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
 //   KC: __device__ const uint16_t* b_row(const TileCoord&, int n) const;   start of B row n (clamped)
 //   NC: __device__ int b_row_id(const TileCoord&, int k) const;  number of the row that holds k (clamped), and
@@ -116,11 +117,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
     const uint16_t* pb[LB];   // KC: fixed row pointers, advanced by k.  NC: unused (rows change with k)
   };
   const int lr8 = lane >> 3;
-  auto next_tile = [&](int& wg, TileCoord& t) -> bool {
-    for (; wg < n_tiles_bound; wg += gridDim.x)
-      if (p.locate(wg, t)) return true;
-    return false;
-  };
+  // locate() answers false only when the workgroup's XCD has no tile with this or any larger id
+  auto next_tile = [&](int& wg, TileCoord& t) -> bool { return wg < n_tiles_bound && p.locate(wg, t); };
   auto setup = [&](Loads& L, const TileCoord& t) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
@@ -311,32 +309,87 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
   }
 }
 
-// ---- tile schedule shared by the token-major problems ----------------------------------------
-// XCD x works through the groups g with g % 8 == x, in ascending order.  grp[x][i] = (group, number of
-// m tiles of the groups before it in this XCD's list); an end entry (-1, total m tiles) closes the list.
-// Inside a group the m tiles vary fastest, so that the tiles that share a B panel (one n tile of the
-// group's block) run at the same time and the panel is read from HBM once.
+// ---- tile schedule shared by the grouped problems ----------------------------------------------
+// Every non-empty group (block of neurons with its tokens) is given to one XCD; XCD x works through its list
+// in order.  grp[x][i] = (group, number of m tiles of the groups before it in this list); an end entry
+// (-1, total m tiles) closes the list.  Inside a group the m tiles vary fastest, so that the tiles that share a
+// B panel (one n tile of the group's block) run at the same time and the panel is read from HBM once.
+//
+// Groups differ in size (the router does not balance them), so they are dealt out longest first, each to the
+// XCD with the least work so far (ties to the lower XCD); the work of a group is counted in 64-row units plus
+// a constant for the per-tile overhead, which balances both the token-major tile counts and the contraction
+// lengths of the neuron-major problems.  Which XCD computes a group has no influence on any result.
 struct TokenSched {
-  const int2* grp;       // [kXcd][cap_groups + 1]
+  const int2* grp;       // [kXcd][cap]
   const int* len;        // [kXcd] number of groups in the list
-  int cap;               // entries per XCD (groups + 1)
-  int max_tiles;         // upper bound of m tiles per XCD (for the grid size)
+  int cap;               // entries per XCD (n_groups + 1)
+  int max_tiles;         // upper bound of m tiles of one XCD (for the tile-id bound of a launch)
 };
 
-// One thread per XCD lists its groups.
-__global__ void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups, int cap,
-                                   int2* __restrict__ grp, int* __restrict__ len) {
-  const int x = threadIdx.x;
-  if (x >= kXcd) return;
-  int n = 0, tiles = 0;
-  for (int g = x; g < n_groups; g += kXcd) {
-    const int rows = group_off[g + 1] - group_off[g];
-    if (rows == 0) continue;
-    grp[(size_t)x * cap + n++] = make_int2(g, tiles);
-    tiles += (rows + kTM - 1) / kTM;
+constexpr int kSchedSortMax = 1024;   // up to this many groups are dealt out longest first; more: round-robin
+
+// One workgroup of 1024 threads.
+__global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups,
+                                                           int cap, int2* __restrict__ grp, int* __restrict__ len) {
+  __shared__ int s_rows[kSchedSortMax];
+  __shared__ int s_order[kSchedSortMax];
+  __shared__ int s_sorted[kSchedSortMax];
+  const int tid = threadIdx.x;
+  if (n_groups <= kSchedSortMax) {
+    int rows = 0;
+    if (tid < n_groups) { rows = group_off[tid + 1] - group_off[tid]; s_rows[tid] = rows; }
+    const int n_full = __syncthreads_count(rows > 0);   // non-empty groups; also orders the writes above
+    if (tid < n_groups) {
+      int rank = 0;   // position in the order (rows descending, group id ascending): a permutation
+      for (int g = 0; g < n_groups; ++g) {
+        const int r = s_rows[g];
+        rank += (r > rows || (r == rows && g < tid)) ? 1 : 0;
+      }
+      s_order[rank] = tid;
+      s_sorted[rank] = rows;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int load[kXcd], n[kXcd], tiles[kXcd];
+#pragma unroll
+      for (int x = 0; x < kXcd; ++x) { load[x] = 0; n[x] = 0; tiles[x] = 0; }
+      for (int i = 0; i < n_full; ++i) {   // descending order: the non-empty groups come first
+        const int g = s_order[i], r = s_sorted[i];
+        int best = 0, least = load[0];   // no run-time array index: the counters stay in registers
+#pragma unroll
+        for (int x = 1; x < kXcd; ++x) {
+          const bool lt = load[x] < least;
+          best = lt ? x : best;
+          least = lt ? load[x] : least;
+        }
+#pragma unroll
+        for (int x = 0; x < kXcd; ++x) {   // constant indices keep the counters in registers
+          if (x == best) {
+            grp[(size_t)x * cap + n[x]] = make_int2(g, tiles[x]);
+            n[x] += 1;
+            tiles[x] += (r + kTM - 1) / kTM;
+            load[x] += (r + 63) / 64 + 2;
+          }
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < kXcd; ++x) {
+        grp[(size_t)x * cap + n[x]] = make_int2(-1, tiles[x]);
+        len[x] = n[x];
+      }
+    }
+  } else if (tid < kXcd) {
+    const int x = tid;
+    int n = 0, tiles = 0;
+    for (int g = x; g < n_groups; g += kXcd) {
+      const int rows = group_off[g + 1] - group_off[g];
+      if (rows == 0) continue;
+      grp[(size_t)x * cap + n++] = make_int2(g, tiles);
+      tiles += (rows + kTM - 1) / kTM;
+    }
+    grp[(size_t)x * cap + n] = make_int2(-1, tiles);
+    len[x] = n;
   }
-  grp[(size_t)x * cap + n] = make_int2(-1, tiles);
-  len[x] = n;
 }
 
 __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,

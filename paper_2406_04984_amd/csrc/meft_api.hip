@@ -95,9 +95,14 @@ bool use_dense(const meft_shape& s) {
 }
 
 int round64(int v) { return (v + 63) & ~63; }
-// per XCD: at most ceil(n_blocks/8) groups (+1 end entry) and this many m tiles
-int sched_cap(const meft_shape& s) { return (s.n_blocks + kXcd - 1) / kXcd + 1; }
-int sched_max_tiles(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + (s.n_blocks + kXcd - 1) / kXcd + 1); }
+// per XCD: at most n_blocks groups (+1 end entry) and, as a bound that needs no knowledge of the deal, all m tiles
+int sched_cap(const meft_shape& s) { return s.n_blocks + 1; }
+int sched_max_tiles(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + s.n_blocks); }
+// bound of the tile ids of a launch with tn n tiles per m tile (ids beyond the real ones find no tile)
+int tile_bound(const meft_shape& s, int tn) {
+  const int64_t b = (int64_t)kXcd * sched_max_tiles(s) * tn;
+  return (int)(b < (int64_t)INT32_MAX ? b : (int64_t)INT32_MAX);
+}
 
 constexpr int kRouterSplitMax = 4;
 
@@ -353,7 +358,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
   if (dense) {
     MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
                 s.n_blocks, s.top_e, w.tok_of_slot, w.slot_of_ent, w.goffp);
-    MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(64), 0, st, w.group_off, s.n_blocks,
+    MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks,
                 sched_cap(s), w.sched_pairs, w.sched_len);
   }
 }
@@ -395,7 +400,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokKC<false> ps{};
     ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
     ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
-    launch_gemm_mfma("score_gemm", ps, kXcd * sched.max_tiles * ((s.block_size + kTN - 1) / kTN), st);
+    launch_gemm_mfma("score_gemm", ps, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
   } else {
     GemmNTArgs a{};
     a.A = h; a.Bm = K; a.C = w.sc; a.perm = w.perm; a.group_off = w.group_off; a.tile_off = w.tile_off;
@@ -412,7 +417,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokNC pv{};
     pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
     pv.d = s.d; pv.part = w.part;
-    launch_gemm_mfma("value_gemm", pv, kXcd * sched.max_tiles * ((s.d + kTN - 1) / kTN), st);
+    launch_gemm_mfma("value_gemm", pv, tile_bound(s, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(s, w.part, w, out, st);
   } else if (s.dtype == MEFT_BF16) {
     launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
@@ -452,20 +457,21 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokKC<true> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
     pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
-    launch_gemm_mfma("dact_gemm", pg, kXcd * sched.max_tiles * ((s.block_size + kTN - 1) / kTN), st);
+    launch_gemm_mfma("dact_gemm", pg, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
     if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     if (dh) {
       ProbTokNC ph{};
       ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
       ph.d = s.d; ph.part = w.part;
-      launch_gemm_mfma("dh_gemm", ph, kXcd * sched.max_tiles * ((s.d + kTN - 1) / kTN), st);
+      launch_gemm_mfma("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
-    const int neu_grid = kXcd * ((s.n_blocks + kXcd - 1) / kXcd) * ((s.block_size + kTM - 1) / kTM) *
-                         ((s.d + kTN - 1) / kTN);
+    // every listed group has the same tiles; in the worst case one XCD holds all groups
+    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
+    const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
     ProbNeuNC pn{};
     pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
-    pn.n_groups = s.n_blocks; pn.bs = s.block_size; pn.d = s.d;
+    pn.sched = sched; pn.bs = s.block_size; pn.d = s.d;
     pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
     launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
     pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
