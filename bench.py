@@ -51,6 +51,33 @@ def kernel_models(cfg):
     }
 
 
+# profiler name of the kernel behind each stage label (the rocprofv3 summaries list kernels by symbol)
+STAGE_SYMBOL = {
+    "router_gemm": "gemm_mfma_kernel<ProbRouter>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<false> >",
+    "dact_gemm": "gemm_mfma_kernel<ProbTokKC<true> >", "value_gemm": "gemm_mfma_kernel<ProbTokNC>",
+    "dh_gemm": "gemm_mfma_kernel<ProbTokNC>", "dV_gemm": "gemm_mfma_kernel<ProbNeuNC>",
+    "dK_gemm": "gemm_mfma_kernel<ProbNeuNC>", "topk_select": "topk_select_kernel",
+}
+
+
+def profiled_traffic(workload, stage):
+    """HBM bytes per launch (read + written) of a stage's kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    summary committed under profiles/ for this workload; None when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_all_kernels.md")
+    sym = STAGE_SYMBOL.get(stage)
+    if sym is None or not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 6 and cells[0] == sym:
+            try:
+                return {"read_bytes": float(cells[4]) * 1e6, "written_bytes": float(cells[5]) * 1e6,
+                        "source": f"profiles/{workload}_all_kernels.md"}
+            except ValueError:
+                return None
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,8 +161,8 @@ def main() -> int:
         if cfg.dtype == "f32":
             bound, peak = "alu", FP32_VALU_PEAK_TFLOPS
     roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 2), "peak": peak,
-                "unit": runit, "frac": round(achieved / peak, 4), "traffic": None,
-                "avg_launch_ms": round(kern[dominant], 4)}
+                "unit": runit, "frac": round(achieved / peak, 4),
+                "traffic": profiled_traffic(cfg.name, dominant), "avg_launch_ms": round(kern[dominant], 4)}
     if cfg.host_kv:
         # keys/values in pinned host memory: the step is bound by the host link.  Bytes: every block in use of K and
         # V goes host->device in the forward and again in the backward, the touched rows of dK and dV go back.
