@@ -26,6 +26,14 @@
  *   7. dV[j,:] += max(sc[j],0) dOut[t,:];  dK[j,:] += ds[j] h[t,:];  dh[t,:] += ds[j] K[j,:]
  *   8. touched = sorted unique union of the I_t; every other row of dK, dV is zero.
  *
+ * Optimizer step (Section 4.3 "Implementation Details": the Adam optimizer; Section 3.1, last
+ * paragraph: only the activated rows have a gradient and are updated), meft_oracle_adam_rows:
+ * for every row j of `touched` and every column c, with step count t >= 1,
+ *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+ *   w = w - lr (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps)            (Adam as published)
+ * Rows outside `touched` keep weights and both moments unchanged (reading: a row without a
+ * gradient in a step takes no part in that step; t counts steps of the layer, not of the row).
+ *
  * Inputs are float32 arrays that hold exactly the stored values (bf16 values
  * are exactly representable); every product and sum is done in double, sums in
  * ascending index order.
@@ -41,7 +49,9 @@
  * top_e = n_blocks and top_k = N (values and all three gradients), block-dense
  * and saturation cases, one-expert and one-neuron-per-expert special cases,
  * stable-argsort top-k, constructed ties, finite differences, linearity, a
- * hand-worked example (tests/golden/worked_example.txt).
+ * hand-worked example (tests/golden/worked_example.txt).  Adam: closed form of the first step,
+ * torch.optim.Adam (all rows touched) and torch.optim.SparseAdam (row subsets, eps -> 0) over
+ * several steps, untouched rows bit-identical.
  */
 #include <math.h>
 #include <stdint.h>
@@ -270,6 +280,29 @@ int meft_oracle_apply(const oracle_shape* s, const float* h, const float* K, con
       const double a = sc > 0.0 ? sc : 0.0;
       const float* vj = V + (size_t)j * d;
       for (int32_t c = 0; c < d; ++c) ot[c] += a * (double)vj[c];
+    }
+  }
+  return 0;
+}
+
+/* Row-sparse Adam step on the rows listed in `touched` (ascending, unique).  All arrays [N, d], double. */
+int meft_oracle_adam_rows(int32_t N, int32_t d, const int32_t* touched, int32_t n_touched, const double* g,
+                          double* w, double* m, double* v, double lr, double b1, double b2, double eps,
+                          int32_t step) {
+  if (N < 1 || d < 1 || n_touched < 0 || n_touched > N || step < 1) return 1;
+  for (int32_t i = 0; i < n_touched; ++i)
+    if (touched[i] < 0 || touched[i] >= N || (i > 0 && touched[i] <= touched[i - 1])) return 2;
+  const double c1 = 1.0 - pow(b1, (double)step), c2 = 1.0 - pow(b2, (double)step);
+#pragma omp parallel for schedule(static)
+  for (int32_t i = 0; i < n_touched; ++i) {
+    const size_t o = (size_t)touched[i] * d;
+    for (int32_t c = 0; c < d; ++c) {
+      const double gr = g[o + c];
+      const double mn = b1 * m[o + c] + (1.0 - b1) * gr;
+      const double vn = b2 * v[o + c] + (1.0 - b2) * gr * gr;
+      m[o + c] = mn;
+      v[o + c] = vn;
+      w[o + c] -= lr * (mn / c1) / (sqrt(vn / c2) + eps);
     }
   }
   return 0;

@@ -38,7 +38,7 @@ def _load():
     if _lib is None:
         _lib = ctypes.CDLL(build())
         for fn in ("meft_oracle_route", "meft_oracle_fwd", "meft_oracle_bwd", "meft_oracle_apply",
-                   "meft_oracle_threads"):
+                   "meft_oracle_threads", "meft_oracle_adam_rows"):
             getattr(_lib, fn).restype = ctypes.c_int
     return _lib
 
@@ -181,3 +181,22 @@ def layer(t, want_candidates=False, rows=None):
     f = forward(t.h, t.K, t.V, r.block_idx, c.block_size, c.top_k, want_candidates)
     b = backward(t.h, t.K, t.V, f.idx, f.score, t.dOut, c.block_size, rows=rows)
     return r, f, b
+
+
+def adam_rows(w, g, m, v, touched, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One row-sparse Adam step; returns new (w, m, v) as float64 arrays, inputs are not modified."""
+    w = np.array(w, dtype=np.float64, order="C")
+    m = np.array(m, dtype=np.float64, order="C")
+    v = np.array(v, dtype=np.float64, order="C")
+    g = np.ascontiguousarray(g, dtype=np.float64)
+    touched = np.ascontiguousarray(touched, dtype=np.int32)
+    N, d = w.shape
+    assert g.shape == w.shape == m.shape == v.shape
+    fn = _load().meft_oracle_adam_rows
+    fn.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_double,
+                   ctypes.c_double, ctypes.c_double, ctypes.c_int32]
+    rc = fn(N, d, _ptr(touched), len(touched), _ptr(g), _ptr(w), _ptr(m), _ptr(v), lr, beta1, beta2, eps, step)
+    if rc:
+        raise ValueError(f"meft_oracle_adam_rows: bad arguments ({rc})")
+    return w, m, v
