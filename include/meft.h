@@ -157,6 +157,45 @@ void meft_profile_enable(int on);
 int meft_profile_read(const char** names, int32_t* launches, float* total_ms, int cap);
 
 /*
+ * Diagnostics: the runtime's description of the launch failure behind the calling thread's most recent
+ * MEFT_ERR_DEVICE from a launch ("no error" if there was none).  Static string, never NULL.
+ */
+const char* meft_last_device_error(void);
+
+/*
+ * Hyper-parameters of one optimizer step.  The paper trains with Adam (Section 4.3, "Implementation
+ * Details"); the learning-rate schedule is the caller's, `lr` is the rate of this step.  `step` counts the
+ * optimizer steps of the layer from 1 and drives both bias corrections.
+ */
+typedef struct {
+  float lr, beta1, beta2, eps;   /* 0 <= beta < 1, eps >= 0 */
+  int32_t step;                  /* >= 1 */
+} meft_adam;
+
+/*
+ * Row-sparse Adam step on one parameter matrix of the adapter (K with G = dK, or V with G = dV).
+ * Section 3.1, last paragraph: only the activated parameters have a gradient; those rows, as listed by
+ * meft_sparse_bwd in `touched`, are updated, every other row keeps its weights and both moments unchanged
+ * (a row without a gradient takes no part in the step).  For each listed row j and column c:
+ *     m = beta1 m + (1 - beta1) g;   v = beta2 v + (1 - beta2) g^2
+ *     w = w - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * computed in fp32.
+ *   W       [N, d] of shape->dtype, device, updated in place on the listed rows
+ *   G       [N, d] of shape->dtype, device, read on the listed rows only
+ *   m, v    [N, d] float, device: first and second moment, updated in place on the listed rows
+ *   master  [N, d] float or NULL, device: if given, it holds the weights in fp32; the step reads and updates
+ *           it and writes its rounding to W (so steps smaller than a bf16 ulp are not lost)
+ *   touched, n_touched   device, as written by meft_sparse_bwd (ascending ids; ids outside [0, N) are skipped)
+ * Uses shape->N, d, dtype (and T, top_k for the launch size); no workspace; enqueues on `stream`, allocates
+ * and synchronises nothing.  All matrices row-major, 16-byte aligned.
+ * Errors: MEFT_ERR_INVALID_ARG (null or misaligned pointer, bad hyper-parameter, bad shape),
+ * MEFT_ERR_UNSUPPORTED (MEFT_FLAG_HOST_KV: host-resident parameters are updated by the host),
+ * MEFT_ERR_DEVICE (launch failure).
+ */
+meft_status meft_adam_rows(const meft_shape* shape, const meft_adam* hp, void* W, const void* G, float* m, float* v,
+                           float* master, const int32_t* touched, const int32_t* n_touched, void* stream);
+
+/*
  * Measurement aid (not part of the paper's method): a plain streaming copy of `bytes` bytes
  * (a multiple of 16; both pointers 16-byte aligned device memory) as one kernel on `stream`.
  * Gives the copy bandwidth of the machine and a dispatch of known traffic against which hardware

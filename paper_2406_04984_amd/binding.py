@@ -19,7 +19,7 @@ MEFT_FLAG_HOST_KV = 1
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
-           "meft_probe_copy")
+           "meft_probe_copy", "meft_adam_rows", "meft_last_device_error")
 
 
 class MeftShape(ctypes.Structure):
@@ -29,15 +29,26 @@ class MeftShape(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("activation", ctypes.c_int32), ("flags", ctypes.c_uint32)]
 
 
+class MeftAdam(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("step", ctypes.c_int32)]
+
+
 class MeftError(RuntimeError):
     def __init__(self, fn: str, status: int):
         self.status = status
-        super().__init__(f"{fn}: {status_string(status)} (status {status})")
+        detail = f": {last_device_error()}" if status == MEFT_ERR_DEVICE else ""
+        super().__init__(f"{fn}: {status_string(status)} (status {status}){detail}")
 
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2406_04984_amd.build` "
                       "(there is no fallback path)")
+# The library must bind to the HIP runtime that the caller's tensors and streams come from.  PyTorch ships its
+# own copy; loading it first makes the loader resolve libmeft.so's dependency to that same copy (two runtimes
+# in one process do not see each other's device memory, and the second one may not find the device at all).
+import torch  # noqa: E402,F401
+
 _lib = ctypes.CDLL(LIB_PATH)
 
 _vp, _sz, _i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
@@ -54,6 +65,10 @@ _lib.meft_sparse_fwd.restype = ctypes.c_int
 _lib.meft_sparse_fwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_sparse_bwd.restype = ctypes.c_int
 _lib.meft_sparse_bwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.meft_adam_rows.restype = ctypes.c_int
+_lib.meft_adam_rows.argtypes = [_shape_p, ctypes.POINTER(MeftAdam), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.meft_last_device_error.restype = ctypes.c_char_p
+_lib.meft_last_device_error.argtypes = []
 _lib.meft_probe_copy.restype = ctypes.c_int
 _lib.meft_probe_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.meft_profile_enable.restype = None
@@ -67,6 +82,10 @@ def make_shape(T, d, n_blocks, block_size, top_e, top_k, dtype, flags=0, N=None,
     dt = {"f32": MEFT_F32, "bf16": MEFT_BF16}.get(dtype, dtype)
     return MeftShape(T, d, n_blocks * block_size if N is None else N, n_blocks, block_size, top_e, top_k,
                      dt, activation, flags)
+
+
+def last_device_error() -> str:
+    return _lib.meft_last_device_error().decode()
 
 
 def status_string(status: int) -> str:
@@ -128,6 +147,14 @@ def meft_sparse_bwd(shape, h, K, V, idx, act, dOut, dh, dK, dV, touched, n_touch
                               _p(dK), _p(dV), _p(touched), _p(n_touched), wp, wb, _stream(stream))
     if check and rc:
         raise MeftError("meft_sparse_bwd", rc)
+    return rc
+
+
+def meft_adam_rows(shape, hp: MeftAdam, W, G, m, v, master, touched, n_touched, stream=None, check=True) -> int:
+    rc = _lib.meft_adam_rows(ctypes.byref(shape), ctypes.byref(hp) if hp is not None else None, _p(W), _p(G),
+                             _p(m), _p(v), _p(master), _p(touched), _p(n_touched), _stream(stream))
+    if check and rc:
+        raise MeftError("meft_adam_rows", rc)
     return rc
 
 

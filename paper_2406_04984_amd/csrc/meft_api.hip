@@ -3,12 +3,14 @@
 // the kernels of the headers included below.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <string>
 #include <vector>
 
 #include "../../include/meft.h"
+#include "adam.h"
 #include "common.h"
 #include "dense_path.h"
 #include "gather.h"
@@ -274,7 +276,16 @@ meft_status check_ws(const meft_shape& s, const void* ws, size_t have) {
   return MEFT_OK;
 }
 
-meft_status launch_status() { return hipGetLastError() == hipSuccess ? MEFT_OK : MEFT_ERR_DEVICE; }
+thread_local hipError_t g_last_device_error = hipSuccess;   // what the last MEFT_ERR_DEVICE of this thread was
+meft_status launch_status() {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return MEFT_OK;
+  g_last_device_error = e;
+  return MEFT_ERR_DEVICE;
+}
+// The runtime keeps the last error of the thread until it is read: an entry point reads it away before its first
+// launch, so that MEFT_ERR_DEVICE reports this call's own launches and not a failure some other code left behind.
+void clear_stale_error() { (void)hipGetLastError(); }
 
 // threads per workgroup and 8-column groups per thread for the row kernels
 void row_launch(int d, int& nthr, int& nv) {
@@ -531,6 +542,7 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
   int n_part = 1;
 
   if (s.dtype == MEFT_BF16 && s.d % kTK == 0) {
@@ -563,6 +575,7 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
   if (!(s.flags & MEFT_FLAG_HOST_KV)) return fwd_impl(s, h, K, V, block_idx, out, idx, act, w, st, nullptr, nullptr);
 
   // K, V in pinned host memory: find the blocks in use, fetch them on the side stream (K first, then V) while
@@ -592,6 +605,7 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   BwdWs w(s, ws);
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
   if (s.T == 0) {
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3(1), dim3(64), 0, st, n_touched, (size_t)1, 0);
     return launch_status();
@@ -624,14 +638,50 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   return launch_status();
 }
 
+meft_status meft_adam_rows(const meft_shape* shape, const meft_adam* hp, void* W, const void* G, float* m,
+                           float* v, float* master, const int32_t* touched, const int32_t* n_touched,
+                           void* stream) {
+  const meft_status cs = check_shape(shape);
+  if (cs != MEFT_OK) return cs;
+  const meft_shape& s = *shape;
+  if (s.flags & MEFT_FLAG_HOST_KV) return MEFT_ERR_UNSUPPORTED;   // the kernel reads and writes device memory
+  if (!hp || !W || !G || !m || !v || !touched || !n_touched) return MEFT_ERR_INVALID_ARG;
+  if (!aligned16(W) || !aligned16(G) || !aligned16(m) || !aligned16(v) || (master && !aligned16(master)))
+    return MEFT_ERR_INVALID_ARG;
+  if (hp->step < 1 || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) ||
+      !(hp->eps >= 0.f) || !(hp->lr == hp->lr))
+    return MEFT_ERR_INVALID_ARG;
+  if (s.T == 0) return MEFT_OK;
+  AdamScalars a;
+  const double b1 = hp->beta1, b2 = hp->beta2;
+  a.lr = hp->lr; a.b1 = hp->beta1; a.b2 = hp->beta2; a.eps = hp->eps;
+  a.omb1 = (float)(1.0 - b1); a.omb2 = (float)(1.0 - b2);
+  a.inv_c1 = (float)(1.0 / (1.0 - std::pow(b1, (double)hp->step)));
+  a.inv_c2 = (float)(1.0 / (1.0 - std::pow(b2, (double)hp->step)));
+  const int64_t cap = (int64_t)s.T * s.top_k < (int64_t)s.N ? (int64_t)s.T * s.top_k : (int64_t)s.N;
+  const int grid = (int)(cap < 4096 ? cap : 4096);   // rows are walked with a grid stride
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
+  if (s.dtype == MEFT_BF16)
+    MEFT_LAUNCH("adam_rows", adam_rows_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, static_cast<bf16_t*>(W),
+                static_cast<const bf16_t*>(G), m, v, master, touched, n_touched, s.N, s.d, a);
+  else
+    MEFT_LAUNCH("adam_rows", adam_rows_kernel<float>, dim3(grid), dim3(256), 0, st, static_cast<float*>(W),
+                static_cast<const float*>(G), m, v, master, touched, n_touched, s.N, s.d, a);
+  return launch_status();
+}
+
 meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0) return MEFT_ERR_INVALID_ARG;
   if (bytes == 0) return MEFT_OK;
   const size_t n = bytes / 16;
+  clear_stale_error();
   MEFT_LAUNCH("probe_copy", probe_copy_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
               static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n);
   return launch_status();
 }
+
+const char* meft_last_device_error(void) { return hipGetErrorString(g_last_device_error); }
 
 void meft_profile_enable(int on) {
   for (auto& e : g_prof) {

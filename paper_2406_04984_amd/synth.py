@@ -180,3 +180,28 @@ def small_case(T: int, d: int, n_blocks: int, block_size: int, top_e: int, top_k
     """An ad-hoc configuration for unit tests."""
     return Config(f"case_T{T}_d{d}_B{n_blocks}x{block_size}_e{top_e}_k{top_k}_{dtype}_s{seed}",
                   dtype, T, d, n_blocks, block_size, top_e, top_k, seed=seed, **kw)
+
+
+@dataclasses.dataclass
+class AdamCase:
+    """Inputs of one optimizer step on a parameter matrix: weights, gradient, both moments, the rows to update.
+    Float arrays hold exactly the stored values (bf16-representable where dtype is "bf16")."""
+    dtype: str
+    W: np.ndarray         # [N, d] float32
+    G: np.ndarray         # [N, d] float32
+    m: np.ndarray         # [N, d] float32
+    v: np.ndarray         # [N, d] float32, >= 0
+    touched: np.ndarray   # ascending int32 row ids
+
+
+def adam_case(N: int, d: int, n_touched: int, dtype: str = "bf16", seed: int = 11, grad_std: float = 0.05) -> AdamCase:
+    """Weights ~ N(0, 1/d) like the keys and values, gradient ~ N(0, grad_std^2), moments of the size a few
+    earlier steps would have left, and a seeded subset of `n_touched` rows."""
+    W = _normal(seed, 101, (N, d), 1.0 / math.sqrt(d))
+    G = _normal(seed, 102, (N, d), grad_std)
+    m = _normal(seed, 103, (N, d), 0.3 * grad_std)
+    v = np.square(_normal(seed, 104, (N, d), 0.2 * grad_std)) + np.float32((0.1 * grad_std) ** 2)
+    if dtype == "bf16":
+        W, G = bf16_to_f32(bf16_round(W)), bf16_to_f32(bf16_round(G))
+    touched = np.sort(_rng(seed, 105).choice(N, size=n_touched, replace=False)).astype(np.int32)
+    return AdamCase(dtype, W, G, m, v, touched)

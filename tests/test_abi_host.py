@@ -22,7 +22,7 @@ def B():
 def test_every_declared_symbol_is_exported(B):
     header = open(os.path.join(ROOT, "include", "meft.h")).read()
     declared = set(re.findall(r"\b(meft_[a-z_]+)\s*\(", header))
-    declared -= {"meft_status", "meft_dtype", "meft_shape"}
+    declared -= {"meft_status", "meft_dtype", "meft_shape", "meft_adam"}
     assert declared == set(B.EXPORTS)
     lib = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
@@ -93,3 +93,26 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(B):
     assert B.meft_check_shape(host_kv) == B.MEFT_OK
     # the host-resident variant needs room for device copies of K, V and staging for dK, dV
     assert B.meft_workspace_bytes(host_kv) >= B.meft_workspace_bytes(s) + 4 * 32 * 64 * 4
+
+
+def test_adam_rows_validates_on_the_host(B):
+    s = _shape(B)
+    fake = 0x1000
+    ok = B.MeftAdam(1e-4, 0.9, 0.999, 1e-8, 1)
+
+    def call(shape, hp, W=fake, G=fake, m=fake, v=fake, master=None, touched=fake, n=fake):
+        return B._lib.meft_adam_rows(ctypes.byref(shape), ctypes.byref(hp) if hp is not None else None, W, G, m, v,
+                                     master, touched, n, None)
+
+    assert call(s, None) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, ok, W=None) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, ok, m=fake + 8) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, ok, master=fake + 4) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, ok, n=None) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, B.MeftAdam(1e-4, 0.9, 0.999, 1e-8, 0)) == B.MEFT_ERR_INVALID_ARG      # steps count from 1
+    assert call(s, B.MeftAdam(1e-4, 1.0, 0.999, 1e-8, 1)) == B.MEFT_ERR_INVALID_ARG      # beta1 < 1
+    assert call(s, B.MeftAdam(1e-4, 0.9, -0.1, 1e-8, 1)) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, B.MeftAdam(1e-4, 0.9, 0.999, -1.0, 1)) == B.MEFT_ERR_INVALID_ARG
+    assert call(s, B.MeftAdam(float("nan"), 0.9, 0.999, 1e-8, 1)) == B.MEFT_ERR_INVALID_ARG
+    assert call(_shape(B, flags=B.MEFT_FLAG_HOST_KV), ok) == B.MEFT_ERR_UNSUPPORTED
+    assert call(_shape(B, top_e=9), ok) == B.MEFT_ERR_INVALID_ARG
