@@ -26,6 +26,12 @@
  *   7. dV[j,:] += max(sc[j],0) dOut[t,:];  dK[j,:] += ds[j] h[t,:];  dh[t,:] += ds[j] K[j,:]
  *   8. touched = sorted unique union of the I_t; every other row of dK, dV is zero.
  *
+ * Batch-union evaluation (Algorithm 1 as printed, which evaluates the adapter over the union of all
+ * tokens' selections rather than per token), meft_oracle_union_fwd / _bwd:
+ *   S = sorted unique ids of all tokens' selections (built by the caller from step 4's lists)
+ *   out[t,:] = sum_{j in S} max(h[t,:].K[j,:], 0) V[j,:]          for every token t
+ *   backward over the same S with the rules of steps 6-7 applied to every (t, j in S).
+ *
  * Optimizer step (Section 4.3 "Implementation Details": the Adam optimizer; Section 3.1, last
  * paragraph: only the activated rows have a gradient and are updated), meft_oracle_adam_rows:
  * for every row j of `touched` and every column c, with step count t >= 1,
@@ -49,7 +55,9 @@
  * top_e = n_blocks and top_k = N (values and all three gradients), block-dense
  * and saturation cases, one-expert and one-neuron-per-expert special cases,
  * stable-argsort top-k, constructed ties, finite differences, linearity, a
- * hand-worked example (tests/golden/worked_example.txt).  Adam: closed form of the first step,
+ * hand-worked example (tests/golden/worked_example.txt).  Batch union: numpy matmul over the
+ * compacted rows, the dense adapter when S is everything, the per-token result plus the extra
+ * neurons' contributions, finite differences.  Adam: closed form of the first step,
  * torch.optim.Adam (all rows touched) and torch.optim.SparseAdam (row subsets, eps -> 0) over
  * several steps, untouched rows bit-identical.
  */
@@ -303,6 +311,66 @@ int meft_oracle_adam_rows(int32_t N, int32_t d, const int32_t* touched, int32_t 
       m[o + c] = mn;
       v[o + c] = vn;
       w[o + c] -= lr * (mn / c1) / (sqrt(vn / c2) + eps);
+    }
+  }
+  return 0;
+}
+
+/* Batch-union forward: out[t,:] = sum over the nS listed neurons of max(h_t.K_j, 0) V_j (ascending j). */
+int meft_oracle_union_fwd(int32_t T, int32_t d, int32_t N, const float* h, const float* K, const float* V,
+                          const int32_t* S, int32_t nS, double* out) {
+  if (T < 0 || d < 1 || N < 1 || nS < 0 || nS > N) return 1;
+  for (int32_t i = 0; i < nS; ++i)
+    if (S[i] < 0 || S[i] >= N || (i > 0 && S[i] <= S[i - 1])) return 2;
+#pragma omp parallel for schedule(static)
+  for (int32_t t = 0; t < T; ++t) {
+    double* ot = out + (size_t)t * d;
+    for (int32_t c = 0; c < d; ++c) ot[c] = 0.0;
+    for (int32_t i = 0; i < nS; ++i) {
+      const size_t j = (size_t)S[i];
+      const double sc = dot_f32(h + (size_t)t * d, K + j * d, d);
+      if (sc > 0.0)
+        for (int32_t c = 0; c < d; ++c) ot[c] += sc * (double)V[j * d + c];
+    }
+  }
+  return 0;
+}
+
+/* Batch-union backward.  dK, dV are [nS, d]: row i belongs to neuron S[i].  dh may be NULL. */
+int meft_oracle_union_bwd(int32_t T, int32_t d, int32_t N, const float* h, const float* K, const float* V,
+                          const int32_t* S, int32_t nS, const float* dOut, double* dh, double* dK, double* dV) {
+  if (T < 0 || d < 1 || N < 1 || nS < 0 || nS > N) return 1;
+  for (int32_t i = 0; i < nS; ++i)
+    if (S[i] < 0 || S[i] >= N || (i > 0 && S[i] <= S[i - 1])) return 2;
+  /* weight gradients: one neuron at a time, tokens in ascending order */
+#pragma omp parallel for schedule(dynamic, 4)
+  for (int32_t i = 0; i < nS; ++i) {
+    const size_t j = (size_t)S[i];
+    double* dk = dK + (size_t)i * d;
+    double* dv = dV + (size_t)i * d;
+    for (int32_t c = 0; c < d; ++c) { dk[c] = 0.0; dv[c] = 0.0; }
+    for (int32_t t = 0; t < T; ++t) {
+      const double sc = dot_f32(h + (size_t)t * d, K + j * d, d);
+      if (!(sc > 0.0)) continue;                       /* a = 0 and ds = 0 */
+      const double g = dot_f32(dOut + (size_t)t * d, V + j * d, d);
+      for (int32_t c = 0; c < d; ++c) {
+        dv[c] += sc * (double)dOut[(size_t)t * d + c];
+        dk[c] += g * (double)h[(size_t)t * d + c];
+      }
+    }
+  }
+  if (dh) {
+#pragma omp parallel for schedule(static)
+    for (int32_t t = 0; t < T; ++t) {
+      double* o = dh + (size_t)t * d;
+      for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+      for (int32_t i = 0; i < nS; ++i) {
+        const size_t j = (size_t)S[i];
+        const double sc = dot_f32(h + (size_t)t * d, K + j * d, d);
+        if (!(sc > 0.0)) continue;
+        const double g = dot_f32(dOut + (size_t)t * d, V + j * d, d);
+        for (int32_t c = 0; c < d; ++c) o[c] += g * (double)K[j * d + c];
+      }
     }
   }
   return 0;

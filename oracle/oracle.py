@@ -38,7 +38,8 @@ def _load():
     if _lib is None:
         _lib = ctypes.CDLL(build())
         for fn in ("meft_oracle_route", "meft_oracle_fwd", "meft_oracle_bwd", "meft_oracle_apply",
-                   "meft_oracle_threads", "meft_oracle_adam_rows"):
+                   "meft_oracle_threads", "meft_oracle_adam_rows", "meft_oracle_union_fwd",
+                   "meft_oracle_union_bwd"):
             getattr(_lib, fn).restype = ctypes.c_int
     return _lib
 
@@ -200,3 +201,40 @@ def adam_rows(w, g, m, v, touched, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
     if rc:
         raise ValueError(f"meft_oracle_adam_rows: bad arguments ({rc})")
     return w, m, v
+
+
+def union_of(idx) -> np.ndarray:
+    """S of Algorithm 1: the sorted unique neuron ids over all tokens' selections."""
+    return np.unique(np.asarray(idx)).astype(np.int32)
+
+
+def union_forward(h, K, V, S) -> np.ndarray:
+    """Batch-union evaluation: every token uses every neuron of S.  Returns out [T, d] float64."""
+    h, hp = _f32(h)
+    K, kp = _f32(K)
+    V, vp = _f32(V)
+    S = np.ascontiguousarray(S, dtype=np.int32)
+    T, d = h.shape
+    out = np.empty((T, d), np.float64)
+    rc = _load().meft_oracle_union_fwd(T, d, K.shape[0], hp, kp, vp, _ptr(S), len(S), _ptr(out))
+    if rc:
+        raise ValueError(f"meft_oracle_union_fwd: bad arguments ({rc})")
+    return out
+
+
+def union_backward(h, K, V, S, dOut, want_dh=True):
+    """Returns (dh [T, d] or None, dK [len(S), d], dV [len(S), d]) float64; row i of dK, dV is neuron S[i]."""
+    h, hp = _f32(h)
+    K, kp = _f32(K)
+    V, vp = _f32(V)
+    g, gp = _f32(dOut)
+    S = np.ascontiguousarray(S, dtype=np.int32)
+    T, d = h.shape
+    dh = np.empty((T, d), np.float64) if want_dh else None
+    dK = np.empty((len(S), d), np.float64)
+    dV = np.empty((len(S), d), np.float64)
+    rc = _load().meft_oracle_union_bwd(T, d, K.shape[0], hp, kp, vp, _ptr(S), len(S), gp, _ptr(dh), _ptr(dK),
+                                       _ptr(dV))
+    if rc:
+        raise ValueError(f"meft_oracle_union_bwd: bad arguments ({rc})")
+    return dh, dK, dV

@@ -54,9 +54,14 @@ struct ProbRouter {
 };
 
 // Token-major, B contiguous along k: rows = tokens of the group (gathered through perm), columns =
-// the block's neurons.  MASKED = false: key scores, written fp32 by entry.  MASKED = true: the
-// activation gradient, masked by A' > 0, written bf16 both slot-major (DS') and neuron-major (DS'^T).
-template <bool MASKED>
+// the block's neurons.  What is written depends on MODE:
+//   kTokScores: key scores, fp32, by entry.
+//   kTokMasked: the activation gradient, masked by A' > 0, bf16, both slot-major (DS') and neuron-major (DS'^T).
+//   kTokRelu:   ReLU of the scores (Eq. 2 without a selection: the batch-union evaluation of Algorithm 1), bf16,
+//               written through the same two pointers, slot-major and neuron-major.
+constexpr int kTokScores = 0, kTokMasked = 1, kTokRelu = 2;
+
+template <int MODE>
 struct ProbTokKC {
   static constexpr bool kBNC = false;
   const uint16_t* X;          // h (scores) or dOut (activation gradient), [T, d]
@@ -64,8 +69,8 @@ struct ProbTokKC {
   const int32_t* perm; const int32_t* group_off; const int32_t* goffp;
   TokenSched sched;
   int e, bs, bsp, d;
-  float* sc;                  // !MASKED: [T*e, bs]
-  const uint16_t* Ap;         // MASKED: A' [slots, bsp]
+  float* sc;                  // kTokScores: [T*e, bs]
+  const uint16_t* Ap;         // kTokMasked: A' [slots, bsp]
   uint16_t* DS; uint16_t* DST;
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
@@ -81,7 +86,7 @@ struct ProbTokKC {
     return W + ((size_t)tc.g * bs + (n < bs ? n : bs - 1)) * d;
   }
   __device__ void store_rows(const TileCoord& tc, int r0, float* rows, int tid) const {
-    if constexpr (!MASKED) {
+    if constexpr (MODE == kTokScores) {
       // a wave stores one row per step: 64 lanes x 4 floats = the 256 columns of the tile.  The row's entry id is
       // wave-uniform and read through the constant address space (a scalar load).
       const auto* cperm = as_const(perm);
@@ -116,14 +121,20 @@ struct ProbTokKC {
           const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
           x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
         }
-        u32x4 mk = {0u, 0u, 0u, 0u};
-        if (row_in && n < bsp) mk = *reinterpret_cast<const u32x4*>(Ap + (size_t)(tc.slot0 + m) * bsp + n);
-        const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+        if constexpr (MODE == kTokMasked) {
+          u32x4 mk = {0u, 0u, 0u, 0u};
+          if (row_in && n < bsp) mk = *reinterpret_cast<const u32x4*>(Ap + (size_t)(tc.slot0 + m) * bsp + n);
+          const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
 #pragma unroll
-        for (int z = 0; z < 8; ++z) {
-          const uint32_t a16 = (mw[z >> 1] >> (16 * (z & 1))) & 0xFFFFu;
-          const bool on = (a16 & 0x7FFFu) != 0u && (a16 & 0x8000u) == 0u;   // positive, non-zero activation
-          x[z] = on ? x[z] : 0.f;
+          for (int z = 0; z < 8; ++z) {
+            const uint32_t a16 = (mw[z >> 1] >> (16 * (z & 1))) & 0xFFFFu;
+            const bool on = (a16 & 0x7FFFu) != 0u && (a16 & 0x8000u) == 0u;   // positive, non-zero activation
+            x[z] = on ? x[z] : 0.f;
+          }
+        } else {
+          // rows beyond the group and columns beyond the block (computed from clamped operand rows) are zero
+#pragma unroll
+          for (int z = 0; z < 8; ++z) x[z] = (row_in && n + z < bs && x[z] > 0.f) ? x[z] : 0.f;
         }
         if (row_in && n < bsp) Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(DS) + (size_t)(tc.slot0 + m) * bsp + n, x);
         f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};

@@ -408,7 +408,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
                  *vv = static_cast<const uint16_t*>(V);
   if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
   if (dense) {
-    ProbTokKC<false> ps{};
+    ProbTokKC<kTokScores> ps{};
     ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
     ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
     launch_gemm_mfma("score_gemm", ps, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
@@ -465,7 +465,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
                 touched, n_touched);
     const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
-    ProbTokKC<true> pg{};
+    ProbTokKC<kTokMasked> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
     pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
     launch_gemm_mfma("dact_gemm", pg, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
