@@ -116,7 +116,8 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
  *   h         [T, d]           in
  *   K, V      [N, d]           in   keys, values
  *   block_idx [T, top_e] i32   in   distinct block ids per token, any order (as meft_route writes)
- *   out       [T, d]           out  adapter output (the frozen FFN term is the caller's)
+ *   out       [T, d]           out  adapter output (the frozen FFN term is the caller's); NULL: the call stops
+ *                                   after the selection (S2'-S4) and writes only idx and act
  *   idx       [T, top_k] i32   out  selected neuron ids (global), distinct per token, ascending
  *   act       [T, top_k] f32   out  max(score, 0) of idx[t, i]
  * A block id outside [0, n_blocks) or repeated within a token is a caller error; such ids are
@@ -155,6 +156,34 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
  */
 void meft_profile_enable(int on);
 int meft_profile_read(const char** names, int32_t* launches, float* total_ms, int cap);
+
+/*
+ * Batch-union evaluation: Algorithm 1 as printed gathers the selections of all tokens of the batch into one
+ * set S and evaluates the adapter densely over S for every token (the per-token reading of Eq. 1-4 is what
+ * meft_sparse_fwd computes; the two agree when one token is processed, or when everything is selected):
+ *     S = sorted unique ids in idx;   out[t, :] = sum_{j in S} max(h[t,:].K[j,:], 0) V[j, :]
+ * and, in the backward, the rules of Section 3.1 applied to every (token, neuron of S) pair:
+ *     g = dOut[t,:].V[j,:], ds = g if h[t,:].K[j,:] > 0 else 0,
+ *     dV[j,:] = sum_t a dOut[t,:],  dK[j,:] = sum_t ds h[t,:],  dh[t,:] = sum_{j in S} ds K[j,:].
+ * bf16 with d % 64 == 0 only (MEFT_ERR_UNSUPPORTED otherwise, and with MEFT_FLAG_HOST_KV); the activations
+ * enter the matrix cores rounded to bf16.
+ *   idx       [T, top_k] device: the selection (meft_sparse_fwd with out == NULL computes just that)
+ *   out       [T, d] device
+ *   S, n_S    device; forward: outputs, capacity min(N, T*top_k), ascending ids and their count (|S| / top_k
+ *             is the paper's sparsity statistic of Section 3.3); backward: inputs, as the forward wrote them
+ *   dK, dV    [N, d] device: only the rows listed in S are written;  dh [T, d] or NULL
+ *   ws        device workspace of at least meft_union_workspace_bytes(shape) bytes, 256-byte aligned
+ * The backward recomputes the activations from h and K[S]; nothing is carried over in the workspace.
+ * Same conventions as the calls above: caller-owned memory, work enqueued on `stream`, no allocation, no
+ * synchronisation, arguments validated on the host first.  meft_union_workspace_bytes returns 0 for a shape
+ * the variant does not support.
+ */
+size_t meft_union_workspace_bytes(const meft_shape* shape);
+meft_status meft_union_fwd(const meft_shape* shape, const void* h, const void* K, const void* V, const int32_t* idx,
+                           void* out, int32_t* S, int32_t* n_S, void* ws, size_t ws_bytes, void* stream);
+meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K, const void* V, const int32_t* S,
+                           const int32_t* n_S, const void* dOut, void* dh, void* dK, void* dV, void* ws,
+                           size_t ws_bytes, void* stream);
 
 /*
  * Diagnostics: the runtime's description of the launch failure behind the calling thread's most recent

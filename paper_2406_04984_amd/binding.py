@@ -19,7 +19,8 @@ MEFT_FLAG_HOST_KV = 1
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
-           "meft_probe_copy", "meft_adam_rows", "meft_last_device_error")
+           "meft_probe_copy", "meft_adam_rows", "meft_last_device_error",
+           "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd")
 
 
 class MeftShape(ctypes.Structure):
@@ -67,6 +68,12 @@ _lib.meft_sparse_bwd.restype = ctypes.c_int
 _lib.meft_sparse_bwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_adam_rows.restype = ctypes.c_int
 _lib.meft_adam_rows.argtypes = [_shape_p, ctypes.POINTER(MeftAdam), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.meft_union_workspace_bytes.restype = _sz
+_lib.meft_union_workspace_bytes.argtypes = [_shape_p]
+_lib.meft_union_fwd.restype = ctypes.c_int
+_lib.meft_union_fwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.meft_union_bwd.restype = ctypes.c_int
+_lib.meft_union_bwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_last_device_error.restype = ctypes.c_char_p
 _lib.meft_last_device_error.argtypes = []
 _lib.meft_probe_copy.restype = ctypes.c_int
@@ -147,6 +154,28 @@ def meft_sparse_bwd(shape, h, K, V, idx, act, dOut, dh, dK, dV, touched, n_touch
                               _p(dK), _p(dV), _p(touched), _p(n_touched), wp, wb, _stream(stream))
     if check and rc:
         raise MeftError("meft_sparse_bwd", rc)
+    return rc
+
+
+def meft_union_workspace_bytes(shape: MeftShape) -> int:
+    return int(_lib.meft_union_workspace_bytes(ctypes.byref(shape)))
+
+
+def meft_union_fwd(shape, h, K, V, idx, out, S, n_S, ws, stream=None, check=True) -> int:
+    wp, wb = _ws(ws)
+    rc = _lib.meft_union_fwd(ctypes.byref(shape), _p(h), _p(K), _p(V), _p(idx), _p(out), _p(S), _p(n_S), wp, wb,
+                             _stream(stream))
+    if check and rc:
+        raise MeftError("meft_union_fwd", rc)
+    return rc
+
+
+def meft_union_bwd(shape, h, K, V, S, n_S, dOut, dh, dK, dV, ws, stream=None, check=True) -> int:
+    wp, wb = _ws(ws)
+    rc = _lib.meft_union_bwd(ctypes.byref(shape), _p(h), _p(K), _p(V), _p(S), _p(n_S), _p(dOut), _p(dh), _p(dK),
+                             _p(dV), wp, wb, _stream(stream))
+    if check and rc:
+        raise MeftError("meft_union_bwd", rc)
     return rc
 
 

@@ -17,6 +17,7 @@
 #include "gemm_nt.h"
 #include "scatter.h"
 #include "select.h"
+#include "union_path.h"
 
 namespace meft {
 namespace {
@@ -270,6 +271,51 @@ meft_status hostkv_fetch(const meft_shape& s, const int32_t* cnt_dev, const void
   return MEFT_OK;
 }
 
+// ---- batch-union variant: virtual blocks over the compacted rows --------------------------------
+struct UnionGeom {
+  int cap;        // capacity of S: min(N, T*top_k)
+  int vbs, nvb;   // rows per virtual block, number of virtual blocks (nvb * vbs >= cap)
+  meft_shape vs;  // the shape the grouped GEMMs see: nvb blocks of vbs rows, every token in every block
+};
+
+// false: the variant is not available for this shape (it runs on the bf16 matrix-core kernels only)
+bool union_geom(const meft_shape& s, UnionGeom& g) {
+  if (s.dtype != MEFT_BF16 || s.d % kTK != 0 || (s.flags & MEFT_FLAG_HOST_KV)) return false;
+  const int64_t cap = (int64_t)s.T * s.top_k < (int64_t)s.N ? (int64_t)s.T * s.top_k : (int64_t)s.N;
+  g.cap = (int)(cap < 1 ? 1 : cap);
+  g.vbs = g.cap >= 1024 ? 1024 : round64(g.cap);
+  g.nvb = (g.cap + g.vbs - 1) / g.vbs;
+  if (g.nvb > 4096 || (int64_t)g.nvb * (s.T > 0 ? s.T : 1) > ((int64_t)1 << 30)) return false;
+  g.vs = s;
+  g.vs.n_blocks = g.nvb; g.vs.block_size = g.vbs; g.vs.N = g.nvb * g.vbs; g.vs.top_e = g.nvb; g.vs.top_k = 1;
+  return true;
+}
+
+struct UnionWs : DispatchWs {
+  int32_t *flag, *chunk_cnt, *rowflag;
+  uint16_t *Kc, *Vc, *dKc, *dVc, *Ap, *ApT, *DS, *DST, *part;
+  size_t bytes;
+  UnionWs(const meft_shape& s, const UnionGeom& g, void* ws) {
+    Carver c(ws);
+    carve(g.vs, c);
+    const size_t n_ent = (size_t)s.T * g.nvb, rows = (size_t)g.nvb * g.vbs;
+    const size_t slots_p = (size_t)g.nvb * round64(s.T);
+    chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
+    flag = c.take<int32_t>(s.N);
+    rowflag = c.take<int32_t>(rows);
+    Kc = c.take<uint16_t>(rows * s.d);
+    Vc = c.take<uint16_t>(rows * s.d);
+    dKc = c.take<uint16_t>(rows * s.d);
+    dVc = c.take<uint16_t>(rows * s.d);
+    Ap = c.take<uint16_t>(n_ent * g.vbs);
+    ApT = c.take<uint16_t>(slots_p * g.vbs);
+    DS = c.take<uint16_t>(n_ent * g.vbs);
+    DST = c.take<uint16_t>(slots_p * g.vbs);
+    part = c.take<uint16_t>(n_ent * s.d);
+    bytes = c.off < 256 ? 256 : c.off;
+  }
+};
+
 // every entry point asks for the same size, the one meft_workspace_bytes() reports
 meft_status check_ws(const meft_shape& s, const void* ws, size_t have) {
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || have < workspace_bytes(s)) return MEFT_ERR_WORKSPACE;
@@ -423,6 +469,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
   }
   MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
               s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
+  if (!out) return launch_status();   // selection only
   if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
   if (dense) {
     ProbTokNC pv{};
@@ -512,7 +559,120 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
   return launch_status();
 }
 
+// Shared front part of the batch-union forward and backward: index structure from n_S, tile schedule, compacted
+// K and V, and A' = ReLU(h K[S]^T) in both layouts.
+static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& w, const void* h, const void* K,
+                        const void* V, const int32_t* S, const int32_t* n_S, hipStream_t st) {
+  const size_t n_slots = (size_t)g.nvb * s.T, n_rows = (size_t)g.nvb * g.vbs;
+  const size_t n_thr = n_slots > n_rows ? n_slots : n_rows;
+  MEFT_LAUNCH("union_maps", union_maps_kernel, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, n_S, g.cap,
+              s.T, g.vbs, g.nvb, w.sblk, w.perm, w.tok_of_slot, w.slot_of_ent, w.group_off, w.goffp, w.rowflag);
+  MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, g.nvb, sched_cap(g.vs),
+              w.sched_pairs, w.sched_len);
+  const int rows_grid = (int)(n_rows < 4096 ? n_rows : 4096);
+  MEFT_LAUNCH("gather_rows", gather_rows_kernel, dim3(rows_grid), dim3(256), 0, st, static_cast<const uint16_t*>(K),
+              S, n_S, g.cap, s.N, s.d, g.vbs, w.Kc);
+  MEFT_LAUNCH("gather_rows", gather_rows_kernel, dim3(rows_grid), dim3(256), 0, st, static_cast<const uint16_t*>(V),
+              S, n_S, g.cap, s.N, s.d, g.vbs, w.Vc);
+  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(g.vs), sched_max_tiles(g.vs)};
+  ProbTokKC<kTokRelu> pr{};
+  pr.X = static_cast<const uint16_t*>(h); pr.W = w.Kc; pr.perm = w.perm; pr.group_off = w.group_off;
+  pr.goffp = w.goffp; pr.sched = sched; pr.e = g.nvb; pr.bs = g.vbs; pr.bsp = g.vbs; pr.d = s.d;
+  pr.DS = w.Ap; pr.DST = w.ApT;
+  launch_gemm_mfma("union_score_gemm", pr, tile_bound(g.vs, (g.vbs + kTN - 1) / kTN), st);
+}
+
 extern "C" {
+
+size_t meft_union_workspace_bytes(const meft_shape* shape) {
+  UnionGeom g;
+  if (check_shape(shape) != MEFT_OK || !union_geom(*shape, g)) return 0;
+  return UnionWs(*shape, g, nullptr).bytes;
+}
+
+meft_status meft_union_fwd(const meft_shape* shape, const void* h, const void* K, const void* V, const int32_t* idx,
+                           void* out, int32_t* S, int32_t* n_S, void* ws, size_t ws_bytes, void* stream) {
+  meft_status rc = check_shape(shape);
+  if (rc != MEFT_OK) return rc;
+  const meft_shape& s = *shape;
+  UnionGeom g;
+  if (!union_geom(s, g)) return MEFT_ERR_UNSUPPORTED;
+  if (!h || !K || !V || !idx || !out || !S || !n_S) return MEFT_ERR_INVALID_ARG;
+  if (!aligned16(h) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return MEFT_ERR_INVALID_ARG;
+  const UnionWs w(s, g, ws);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return MEFT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
+  if (s.T == 0) {
+    MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3(1), dim3(64), 0, st, n_S, (size_t)1, 0);
+    return launch_status();
+  }
+  // S = ascending ids of the neurons that some token selected
+  const int P = s.T * s.top_k;
+  MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)(((size_t)s.N + 255) / 256)), dim3(256), 0, st, w.flag,
+              (size_t)s.N, 0);
+  MEFT_LAUNCH("mark_idx", mark_idx_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.flag);
+  const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
+  MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
+  MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt, S,
+              n_S);
+  union_front(s, g, w, h, K, V, S, n_S, st);
+  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(g.vs), sched_max_tiles(g.vs)};
+  ProbTokNC pv{};
+  pv.A = w.Ap; pv.W = w.Vc; pv.group_off = w.group_off; pv.sched = sched; pv.bs = g.vbs; pv.bsp = g.vbs;
+  pv.d = s.d; pv.part = w.part;
+  launch_gemm_mfma("union_value_gemm", pv, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
+  launch_reduce_parts(g.vs, w.part, w, out, st);
+  return launch_status();
+}
+
+meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K, const void* V, const int32_t* S,
+                           const int32_t* n_S, const void* dOut, void* dh, void* dK, void* dV, void* ws,
+                           size_t ws_bytes, void* stream) {
+  meft_status rc = check_shape(shape);
+  if (rc != MEFT_OK) return rc;
+  const meft_shape& s = *shape;
+  UnionGeom g;
+  if (!union_geom(s, g)) return MEFT_ERR_UNSUPPORTED;
+  if (!h || !K || !V || !S || !n_S || !dOut || !dK || !dV) return MEFT_ERR_INVALID_ARG;
+  if (!aligned16(h) || !aligned16(K) || !aligned16(V) || !aligned16(dOut) || !aligned16(dK) || !aligned16(dV) ||
+      (dh && !aligned16(dh)))
+    return MEFT_ERR_INVALID_ARG;
+  const UnionWs w(s, g, ws);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return MEFT_ERR_WORKSPACE;
+  if (s.T == 0) return MEFT_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
+  union_front(s, g, w, h, K, V, S, n_S, st);
+  const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(g.vs), sched_max_tiles(g.vs)};
+  const uint16_t *hh = static_cast<const uint16_t*>(h), *gg = static_cast<const uint16_t*>(dOut);
+  ProbTokKC<kTokMasked> pg{};
+  pg.X = gg; pg.W = w.Vc; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
+  pg.e = g.nvb; pg.bs = g.vbs; pg.bsp = g.vbs; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
+  launch_gemm_mfma("union_dact_gemm", pg, tile_bound(g.vs, (g.vbs + kTN - 1) / kTN), st);
+  if (dh) {
+    ProbTokNC ph{};
+    ph.A = w.DS; ph.W = w.Kc; ph.group_off = w.group_off; ph.sched = sched; ph.bs = g.vbs; ph.bsp = g.vbs;
+    ph.d = s.d; ph.part = w.part;
+    launch_gemm_mfma("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
+    launch_reduce_parts(g.vs, w.part, w, dh, st);
+  }
+  const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
+  const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
+  ProbNeuNC pn{};
+  pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;
+  pn.sched = sched; pn.bs = g.vbs; pn.d = s.d;
+  pn.AT = w.ApT; pn.X = gg; pn.G = w.dVc;
+  launch_gemm_mfma("union_dV_gemm", pn, neu_grid, st);
+  pn.AT = w.DST; pn.X = hh; pn.G = w.dKc;
+  launch_gemm_mfma("union_dK_gemm", pn, neu_grid, st);
+  const int rows_grid = g.cap < 4096 ? g.cap : 4096;
+  MEFT_LAUNCH("scatter_rows", scatter_rows_kernel, dim3(rows_grid), dim3(256), 0, st, w.dVc, S, n_S, s.N, s.d, g.cap,
+              static_cast<uint16_t*>(dV));
+  MEFT_LAUNCH("scatter_rows", scatter_rows_kernel, dim3(rows_grid), dim3(256), 0, st, w.dKc, S, n_S, s.N, s.d, g.cap,
+              static_cast<uint16_t*>(dK));
+  return launch_status();
+}
 
 meft_status meft_check_shape(const meft_shape* shape) { return check_shape(shape); }
 
@@ -569,8 +729,8 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   meft_status rc = check_shape(shape);
   if (rc != MEFT_OK) return rc;
   const meft_shape& s = *shape;
-  if (!h || !K || !V || !block_idx || !out || !idx || !act) return MEFT_ERR_INVALID_ARG;
-  if (!aligned16(h) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return MEFT_ERR_INVALID_ARG;
+  if (!h || !K || !V || !block_idx || !idx || !act) return MEFT_ERR_INVALID_ARG;
+  if (!aligned16(h) || !aligned16(K) || !aligned16(V) || (out && !aligned16(out))) return MEFT_ERR_INVALID_ARG;
   FwdWs w(s, ws);
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;

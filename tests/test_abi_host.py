@@ -116,3 +116,22 @@ def test_adam_rows_validates_on_the_host(B):
     assert call(s, B.MeftAdam(float("nan"), 0.9, 0.999, 1e-8, 1)) == B.MEFT_ERR_INVALID_ARG
     assert call(_shape(B, flags=B.MEFT_FLAG_HOST_KV), ok) == B.MEFT_ERR_UNSUPPORTED
     assert call(_shape(B, top_e=9), ok) == B.MEFT_ERR_INVALID_ARG
+
+
+def test_union_calls_validate_on_the_host(B):
+    s = _shape(B, dtype="bf16")
+    need = B.meft_union_workspace_bytes(s)
+    assert need > 0
+    fake = 0x1000
+    f = B._lib.meft_union_fwd
+    assert f(ctypes.byref(s), None, fake, fake, fake, fake, fake, fake, fake, need, None) == B.MEFT_ERR_INVALID_ARG
+    assert f(ctypes.byref(s), fake, fake, fake, fake, fake, None, fake, fake, need, None) == B.MEFT_ERR_INVALID_ARG
+    assert f(ctypes.byref(s), fake, fake + 2, fake, fake, fake, fake, fake, fake, need, None) == B.MEFT_ERR_INVALID_ARG
+    assert f(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, None, 0, None) == B.MEFT_ERR_WORKSPACE
+    assert f(ctypes.byref(s), fake, fake, fake, fake, fake, fake, fake, fake, need - 1, None) == B.MEFT_ERR_WORKSPACE
+    b = B._lib.meft_union_bwd
+    assert b(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, None, fake, fake, need, None) == B.MEFT_ERR_INVALID_ARG
+    assert b(ctypes.byref(s), fake, fake, fake, fake, fake, fake, None, fake, fake, fake, need - 1, None) == B.MEFT_ERR_WORKSPACE
+    f32 = _shape(B, dtype="f32")
+    assert B.meft_union_workspace_bytes(f32) == 0
+    assert f(ctypes.byref(f32), fake, fake, fake, fake, fake, fake, fake, fake, 1 << 30, None) == B.MEFT_ERR_UNSUPPORTED
