@@ -226,6 +226,32 @@ def main() -> int:
             extra["adam_rows"] = {"ms_per_matrix": round(ms, 4), "rows": nt, "bytes_per_element": per_elem,
                                   "GB/s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
+    # The batch-union evaluation of Algorithm 1 on the same inputs and selections: every token over all of S.
+    ubytes = B.meft_union_workspace_bytes(layer.shape)
+    if ubytes > 0 and not cfg.host_kv:
+        uws = torch.empty((ubytes,), dtype=torch.uint8, device="cuda")
+        S = torch.empty_like(layer.touched)
+        n_S = torch.zeros_like(layer.n_touched)
+        uout = torch.empty_like(layer.out)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for rep in range(2):   # the second repetition is the timed one
+            ev[0].record()
+            B.meft_union_fwd(layer.shape, layer.h, layer.K, layer.V, layer.idx, uout, S, n_S, uws)
+            ev[1].record()
+            B.meft_union_bwd(layer.shape, layer.h, layer.K, layer.V, S, n_S, layer.dOut, layer.dh, layer.dK, layer.dV,
+                             uws)
+            ev[2].record()
+            torch.cuda.synchronize()
+        nS = int(n_S.item())
+        f_ms, b_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+        flop = 2.0 * cfg.T * nS * cfg.d
+        extra["union_variant"] = {"S": nS, "fwd_ms": round(f_ms, 3), "bwd_ms": round(b_ms, 3),
+                                  "tokens/s": round(cfg.T / ((f_ms + b_ms) * 1e-3), 1),
+                                  "fwd_TFLOP/s": round(2 * flop / (f_ms * 1e-3) / 1e12, 1),
+                                  "bwd_TFLOP/s": round(5 * flop / (b_ms * 1e-3) / 1e12, 1),
+                                  "note": "fwd = 2 contractions of 2*T*|S|*d flop, bwd = 5 (activations recomputed)"}
+        del uws, uout
+
     line = {
         "metric": "sparse-adapter fwd+bwd tokens/sec per layer",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
