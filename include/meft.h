@@ -77,7 +77,8 @@ enum { MEFT_FLAG_HOST_KV = 1u };
  *   T >= 0; d, n_blocks, block_size >= 1; N == n_blocks*block_size; 1 <= top_e <= n_blocks;
  *   1 <= top_k <= top_e*block_size; T*top_k and T*top_e*block_size below 2^31; activation == 0.
  * Limits of this build (else MEFT_ERR_UNSUPPORTED):
- *   d a multiple of 8 and at most 16384; top_e*block_size at most 12288; n_blocks at most 16384.
+ *   d a multiple of 8 and at most 16384; top_e*block_size at most 4194304 (up to 12288
+ *   candidates a token's scores are selected from LDS, beyond that from global memory); n_blocks at most 16384.
  */
 typedef struct {
   int32_t T, d, N, n_blocks, block_size;

@@ -57,7 +57,9 @@ struct LaunchScope {
   } while (0)
 
 // ---- shape checks ---------------------------------------------------------------------------
-constexpr int kMaxD = 16384, kMaxC = 12288, kMaxBlocks = 16384;
+constexpr int kMaxD = 16384, kMaxBlocks = 16384;
+constexpr int kMaxC = 1 << 22;      // candidates per token (top_e * block_size)
+constexpr int kMaxLdsC = 12288;     // up to here the top-k selection keeps a token's keys in LDS
 
 meft_status check_shape(const meft_shape* s) {
   if (!s) return MEFT_ERR_INVALID_ARG;
@@ -94,7 +96,8 @@ struct Carver {
 // kernels are used.
 bool use_dense(const meft_shape& s) {
   const int64_t C = (int64_t)s.top_e * s.block_size;
-  return s.dtype == MEFT_BF16 && s.d % kTK == 0 && s.block_size >= 16 && (int64_t)s.top_k * 64 >= C;
+  return s.dtype == MEFT_BF16 && s.d % kTK == 0 && s.block_size >= 16 && (int64_t)s.top_k * 64 >= C &&
+         C <= kMaxLdsC;
 }
 
 int round64(int v) { return (v + 63) & ~63; }
@@ -467,8 +470,12 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     const int nb_used = s.n_blocks < n_ent ? s.n_blocks : n_ent;
     launch_gemm_nt(s, a, n_ent / kGemmBM + nb_used, n_ent / kGemmF32BM + nb_used, "score_gemm", st);
   }
-  MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
-              s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
+  if (C <= kMaxLdsC)
+    MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
+                s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
+  else   // candidate sets beyond LDS (e.g. one block holding every neuron): keys stay in global memory
+    MEFT_LAUNCH("topk_select_big", topk_select_big_kernel, dim3(s.T), dim3(1024), 0, st, w.sc, w.sblk, C,
+                s.block_size, s.top_e, s.top_k, idx, act);
   if (!out) return launch_status();   // selection only
   if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
   if (dense) {

@@ -242,4 +242,86 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const float* __restric
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same selection for candidate sets that do not fit in LDS (the paper's ablation without key experts
+// is one block holding every neuron: Section 4.3 "MEFT w/o KE", Eq. 1-4 over all r neurons).  The scores
+// stay in global memory and are read once per pass: four histogram passes (8 bits each) for the k-th
+// largest key and the number of its equals that belong, then one ordered sweep in tiles of 4096 candidates
+// (thread order = position order inside a tile, a running base across tiles) that emits the selected
+// positions in ascending order.  One workgroup of 1024 threads per token; C % 4 == 0 is not required.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void topk_select_big_kernel(const float* __restrict__ sc,
+                                                               const int32_t* __restrict__ sblk, int C, int bs,
+                                                               int e, int k, int32_t* __restrict__ idx,
+                                                               float* __restrict__ act) {
+  __shared__ int s_hist[256];
+  __shared__ int s_w[16];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const float* row = sc + (size_t)t * C;
+  if (tid == 0) { s_prefix = 0u; s_need = k; }
+  __syncthreads();
+
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) s_hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    for (int i = tid; i < C; i += 1024) {
+      const uint32_t key = order_key(row[i]);
+      if ((key & himask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    // thread `tid` < 256 owns digit 255 - tid, so that an exclusive scan counts the larger digits
+    const int digit = 255 - tid;
+    const int h = tid < 256 ? s_hist[digit] : 0;
+    int tot;
+    const int above = block_excl_scan_1024(h, s_w, tot);
+    const int need = s_need;
+    __syncthreads();
+    if (tid < 256 && above < need && need <= above + h) {
+      s_prefix = prefix | ((uint32_t)digit << shift);
+      s_need = need - above;
+    }
+    __syncthreads();
+  }
+  const uint32_t thr = s_prefix;
+  const int need = s_need;  // how many keys equal to thr are selected (>= 1)
+
+  int gt_base = 0, eq_base = 0;   // selected-or-equal counts in the tiles before this one (same in every thread)
+  for (int base = 0; base < C; base += 4096) {
+    const int i0 = base + tid * 4;
+    uint32_t key[4];
+    int ngt = 0, neq = 0;
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+      key[z] = i0 + z < C ? order_key(row[i0 + z]) : 0u;   // key 0 is below every real key (thr >= a real key)
+      const bool in = i0 + z < C;
+      ngt += in && key[z] > thr;
+      neq += in && key[z] == thr;
+    }
+    int tot_gt, tot_eq;
+    int gt_before = gt_base + block_excl_scan_1024(ngt, s_w, tot_gt);
+    int eq_before = eq_base + block_excl_scan_1024(neq, s_w, tot_eq);
+#pragma unroll
+    for (int z = 0; z < 4; ++z) {
+      if (i0 + z >= C) break;
+      const bool gt = key[z] > thr, eq = key[z] == thr;
+      if (gt || (eq && eq_before < need)) {
+        const int slot = gt_before + min(eq_before, need);  // selected positions before this one
+        const int i = i0 + z;
+        const int q = i / bs, r = i - q * bs;
+        const float v = key_to_float(key[z]);
+        idx[(size_t)t * k + slot] = sblk[(size_t)t * e + q] * bs + r;
+        act[(size_t)t * k + slot] = v > 0.f ? v : 0.f;
+      }
+      gt_before += gt;
+      eq_before += eq;
+    }
+    gt_base += tot_gt;
+    eq_base += tot_eq;
+  }
+}
+
 }  // namespace meft

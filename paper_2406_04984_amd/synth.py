@@ -67,6 +67,9 @@ CONFIGS: Dict[str, Config] = {
                          outlier_frac=0.01, outlier_scale=8.0, seed=BASE_SEED + 2),
     "llama7b_bf16": Config("llama7b_bf16", "bf16", 8192, 4096, 64, 1024, 4, 256,
                            outlier_frac=0.005, outlier_scale=10.0, seed=BASE_SEED + 3),
+    # the paper's ablation without key experts (Section 4.3, "MEFT w/o KE"): one block holds every neuron
+    "noke_bf16": Config("noke_bf16", "bf16", 2048, 4096, 1, 65536, 1, 256,
+                        outlier_frac=0.005, outlier_scale=10.0, seed=BASE_SEED + 6),
     "wide_bf16": Config("wide_bf16", "bf16", 4096, 4096, 256, 1024, 8, 512,
                         zipf_s=1.1, seed=BASE_SEED + 4),
     "llama7b_hostkv_bf16": Config("llama7b_hostkv_bf16", "bf16", 8192, 4096, 128, 1024, 4, 256,

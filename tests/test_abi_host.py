@@ -49,8 +49,10 @@ def test_shape_validation(B):
         s = _shape(B, **kw)
         assert B.meft_check_shape(s) == B.MEFT_ERR_INVALID_ARG, kw
         assert B.meft_workspace_bytes(s) == 0
-    for kw in [dict(d=60), dict(d=16392), dict(block_size=8192, top_e=2, top_k=4, n_blocks=2)]:
+    for kw in [dict(d=60), dict(d=16392), dict(T=1, block_size=1 << 22, top_e=2, top_k=4, n_blocks=2)]:
         assert B.meft_check_shape(_shape(B, **kw)) == B.MEFT_ERR_UNSUPPORTED, kw
+    # 16384 candidates per token: selected from global memory, supported
+    assert B.meft_check_shape(_shape(B, block_size=8192, top_e=2, top_k=4, n_blocks=2)) == B.MEFT_OK
     # T*top_k must stay below 2^31
     assert B.meft_check_shape(_shape(B, T=1 << 30, top_k=4)) == B.MEFT_ERR_INVALID_ARG
 
