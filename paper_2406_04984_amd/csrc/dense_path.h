@@ -21,6 +21,10 @@ namespace meft {
 
 __device__ __forceinline__ int round_up64(int v) { return (v + 63) & ~63; }
 
+// entries (all 0, a valid token) behind the last slot of tok_of_slot, so that look-ups for the padded tail of a
+// group's contraction and the one-k-tile-ahead prefetch of row numbers stay inside the array
+constexpr int kSlotPad = 192;
+
 // ---- problem policies for gemm_mfma_kernel ----------------------------------------------------
 
 // Router scores (Eq. 5): p[T, n_blocks] = h . Wg^T, one group.  The problem is skinny (n_blocks columns), so
@@ -28,6 +32,8 @@ __device__ __forceinline__ int round_up64(int v) { return (v + 63) & ~63; }
 // scores to p + s*T*n_blocks and the top-e kernel adds the partials in a fixed order.
 struct ProbRouter {
   static constexpr bool kBNC = false;
+  static constexpr bool kRowIdsInMemory = false;
+  static constexpr int kStoreBarriers = 0;
   const uint16_t* h; const uint16_t* Wg; float* p;
   int T, d, B, ksplit;
   __device__ bool locate(int wg, TileCoord& tc) const {
@@ -64,6 +70,8 @@ constexpr int kTokScores = 0, kTokMasked = 1, kTokRelu = 2;
 template <int MODE>
 struct ProbTokKC {
   static constexpr bool kBNC = false;
+  static constexpr bool kRowIdsInMemory = false;
+  static constexpr int kStoreBarriers = MODE == kTokScores ? 0 : 1;
   const uint16_t* X;          // h (scores) or dOut (activation gradient), [T, d]
   const uint16_t* W;          // K or V, [N, d]
   const int32_t* perm; const int32_t* group_off; const int32_t* goffp;
@@ -141,7 +149,7 @@ struct ProbTokKC {
         *reinterpret_cast<f32x4*>(&rows[tile_index(r, c)]) = a;
         *reinterpret_cast<f32x4*>(&rows[tile_index(r, c + 4)]) = b;
       }
-      __syncthreads();
+      MEFT_BARRIER_LDS();
       // step 2, neuron-major: column n, 8 consecutive slots -> one 16-byte store into DS'^T
       const int Mgp = round_up64(tc.Mrows);
       uint16_t* base = DST + (size_t)as_const(goffp)[tc.g] * bs;
@@ -163,6 +171,8 @@ struct ProbTokKC {
 // W = K: dh).  A is slot-major [slots, bsp] with zero padding in columns bs..bsp.
 struct ProbTokNC {
   static constexpr bool kBNC = true;
+  static constexpr bool kRowIdsInMemory = false;
+  static constexpr int kStoreBarriers = 0;
   const uint16_t* A;          // A' or DS'
   const uint16_t* W;          // V or K, [N, d]
   const int32_t* group_off;
@@ -178,7 +188,7 @@ struct ProbTokNC {
   __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
     return A + (size_t)(tc.slot0 + (m < tc.Mrows ? m : tc.Mrows - 1)) * bsp;
   }
-  __device__ int b_row_id(const TileCoord& tc, int k) const { return tc.g * bs + (k < bs ? k : bs - 1); }
+  __device__ int b_row_ids(const TileCoord& tc, int k) const { return tc.g * bs + (k < bs ? k : bs - 1); }
   __device__ const uint16_t* b_row_ptr(int row) const { return W + (size_t)row * d; }
   __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
     const int c = (tid & 31) * 8, n = tc.n0 + c;
@@ -200,6 +210,8 @@ struct ProbTokNC {
 // (AT = A'^T, X = dOut: dV;  AT = DS'^T, X = h: dK).  Only rows whose neuron is touched are written.
 struct ProbNeuNC {
   static constexpr bool kBNC = true;
+  static constexpr bool kRowIdsInMemory = true;
+  static constexpr int kStoreBarriers = 0;
   const uint16_t* AT;         // per group [bs, Mgp] at element offset goffp[g]*bs
   const uint16_t* X;          // [T, d]
   const int32_t* group_off; const int32_t* goffp; const int32_t* tok_of_slot;
@@ -223,9 +235,8 @@ struct ProbNeuNC {
   __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
     return AT + (size_t)as_const(goffp)[tc.g] * bs + (size_t)(m < bs ? m : bs - 1) * round_up64(tc.aux);
   }
-  __device__ int b_row_id(const TileCoord& tc, int k) const {   // k is wave-uniform: a scalar load
-    return as_const(tok_of_slot)[tc.slot0 + (k < tc.aux ? k : tc.aux - 1)];
-  }
+  // tok_of_slot is padded by kSlotPad valid entries, which covers k0 + 63 up to the padded contraction length + 127
+  __device__ const int32_t* b_row_id_src(const TileCoord& tc, int k0) const { return tok_of_slot + tc.slot0 + k0; }
   __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }
   __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
     // a wave stores two rows per step (32 lanes x 8 columns each); their touched flags are wave-uniform and
@@ -299,6 +310,8 @@ __global__ __launch_bounds__(256) void slot_maps_kernel(const int32_t* __restric
     const int ent = perm[i];
     tok_of_slot[i] = ent / e;
     slot_of_ent[ent] = i;
+  } else if (i < n_slots + kSlotPad) {
+    tok_of_slot[i] = 0;
   }
   if (blockIdx.x == 0) {
     // serial prefix over groups by one thread per 256-group chunk would need a scan; n_groups is small

@@ -29,7 +29,9 @@ namespace meft {
 
 constexpr int kTM = 128, kTN = 256, kTK = 64, kStages = 3;
 constexpr int kStageElems = (kTM + kTN) * kTK;                 // 24576 bf16 = 48 KB
-constexpr int kGemmLdsBytes = kStages * kStageElems * 2;       // 144 KB
+constexpr int kOperandLdsBytes = kStages * kStageElems * 2;    // 144 KB
+constexpr int kIdRingSlots = 4;                                // k tiles of gathered-row numbers kept per loader
+constexpr int kGemmLdsBytes = kOperandLdsBytes + 2 * kIdRingSlots * 64 * 4;   // + 2 KB
 constexpr int kXcd = 8;
 
 #define MEFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -61,9 +63,16 @@ struct TileCoord {
 //                                                       the same XCD (ids wg + 8, wg + 16, ...)
 //   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
 //   KC: __device__ const uint16_t* b_row(const TileCoord&, int n) const;   start of B row n (clamped)
-//   NC: __device__ int b_row_id(const TileCoord&, int k) const;  number of the row that holds k (clamped), and
+//   static constexpr bool kRowIdsInMemory;              (false for KC)  For NC:
+//       false: __device__ int b_row_ids(const TileCoord&, int k) const;  number of the B row that holds k (plain
+//              arithmetic, no memory access), any valid row for k beyond the contraction length;
+//       true:  __device__ const int32_t* b_row_id_src(const TileCoord&, int k0) const;  where the numbers of the B rows
+//              of k0 .. k0 + 63 are stored (valid rows also beyond the contraction length: those products are zero);
+//              called for k0 up to max(nk, kStages - 1) * 64;  and
 //       __device__ const uint16_t* b_row_ptr(int row) const;      its start
-//   __device__ void store_rows(const TileCoord&, int r0, float* rows, int tid) const;   write tile rows r0..r0+31
+//   __device__ void store_rows(const TileCoord&, int r0, float* rows, int tid) const;   write tile rows r0..r0+31;
+//       executed by the 256 compute threads (tid 0..255); any workgroup barrier inside must be MEFT_BARRIER_LDS()
+//   static constexpr int kStoreBarriers;                number of such barriers in one store_rows call
 //
 // acc[i][j][r] of a wave holds C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,
 // n = wn + j*32 + lane%32 (tile-local); the kernel lays 32 rows at a time out row-major in LDS (tile_index with
@@ -100,73 +109,162 @@ __device__ __forceinline__ void tr_read8(u32x2 (&o)[8], const uint32_t (&alo)[4]
 }
 
 constexpr int kEpiRows = 32;   // rows of the output tile staged through LDS per epilogue pass
+constexpr int kLoaders = 2;    // waves that only request operands (the other four only compute)
+constexpr int kGemmThreads = 256 + 64 * kLoaders;
 
+// Workgroup barrier for the kernel below.  All six waves execute the same sequence of barriers; a compute wave
+// first waits for its own LDS traffic, a loader wave for the operand loads that have to have landed.
+#define MEFT_BARRIER_LDS() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+// Four compute waves (tid 0..255) and kLoaders loader waves.  The loaders own the whole global -> LDS traffic:
+// measured on gfx950 the operand path, not the matrix cores or LDS, bounds these contractions (a compute unit keeps
+// about a hundred 128-byte read requests in flight, no more), and a wave that both requests operands and issues
+// MFMAs keeps neither queue full.  The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ...
+// (gridDim.x is a multiple of 8, so it stays on one XCD's list); the first two operand stages of the next tile are
+// requested before the epilogue of the current one.
 template <class P>
-__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int LA = kTM / 8 / 4;                    // A wave-loads (8 rows x 128 B) per wave and stage: 4
-  constexpr int LB = 8;                              // B wave-loads per wave and stage (KC: 8 rows x 128 B; NC: 2 rows x 512 B)
-
-  // The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ... (gridDim.x is a multiple of 8,
-  // so it stays on one XCD's list).  The first two operand stages of the next tile are requested before the
-  // epilogue of the current one, which hides the fill of the pipeline behind the output stores.
-  struct Loads {
-    const uint16_t* pa[LA];
-    const uint16_t* pb[LB];   // KC: fixed row pointers, advanced by k.  NC: unused (rows change with k)
-  };
-  const int lr8 = lane >> 3;
   // locate() answers false only when the workgroup's XCD has no tile with this or any larger id
   auto next_tile = [&](int& wg, TileCoord& t) -> bool { return wg < n_tiles_bound && p.locate(wg, t); };
-  auto setup = [&](Loads& L, const TileCoord& t) {
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int row = (wave * LA + i) * 8 + lr8;
-      L.pa[i] = p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
-    }
-    if constexpr (!P::kBNC) {
-#pragma unroll
-      for (int i = 0; i < LB; ++i) {
-        const int row = (wave * LB + i) * 8 + lr8;
-        L.pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
-      }
-    }
-  };
-  // NC: the wave's 16 B-row pointers of one k tile.  They are wave-uniform, so any index look-up behind them is a
-  // scalar load (it does not disturb the vector-memory counter that paces the pipeline).  They are fetched one
-  // k tile ahead of their use so that the wait for them is free.
-  struct Rows { int r[2 * LB]; };   // row numbers (32 bits each keep them in scalar registers)
-  auto rows_for = [&](Rows& R, const TileCoord& t, int kt) {
-    if constexpr (P::kBNC) {
-#pragma unroll
-      for (int z = 0; z < 2 * LB; ++z) R.r[z] = p.b_row_id(t, kt * kTK + wave * 2 * LB + z);
-    }
-  };
-  auto issue = [&](const Loads& L, const TileCoord& t, int kt, int stage, const Rows& R) {
-    uint16_t* sa = smem + stage * kStageElems;
-    uint16_t* sb = sa + kTM * kTK;
-#pragma unroll
-    for (int i = 0; i < LA; ++i)
-      __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pa[i] + kt * kTK), MEFT_LPTR(sa + (wave * LA + i) * 8 * kTK), 16, 0, 0);
-    if constexpr (!P::kBNC) {
-#pragma unroll
-      for (int i = 0; i < LB; ++i)
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pb[i] + kt * kTK), MEFT_LPTR(sb + (wave * LB + i) * 8 * kTK), 16, 0, 0);
-    } else {
-#pragma unroll
-      for (int i = 0; i < LB; ++i) {
-        const int krow = 2 * (wave * LB + i) + (lane >> 5);           // this lane's k row inside the tile
-        const int chunk = (lane & 31) ^ (2 * (krow & 7));             // logical 16-byte chunk this lane fetches
-        int col = t.n0 + chunk * 8;
-        col = col > t.Ncols - 8 ? t.Ncols - 8 : col;                  // clamp (columns beyond Ncols are never stored)
-        const uint16_t* src = p.b_row_ptr((lane >> 5) ? R.r[2 * i + 1] : R.r[2 * i]) + col;
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (wave * LB + i) * 512), 16, 0, 0);
-      }
-    }
-  };
+  constexpr int kPasses = kTM / kEpiRows;
 
-  // ---- fragment addressing (the same for every tile) ----
+  int wg = blockIdx.x;
+  TileCoord tc;
+  if (!next_tile(wg, tc)) return;   // the same answer in every wave
+
+  if (wave >= 4) {
+    // ------------------------------------------------------------------ loader waves
+    const int lw = wave - 4;
+    constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (8 rows x 128 B) per loader and stage: 8
+    constexpr int LB = 32 / kLoaders;        // B wave-loads per loader and stage (KC: 8 rows x 128 B; NC: 2 rows x 512 B): 16
+    static_assert(LA + LB <= 63, "partial vmcnt wait out of range");
+    struct Loads {
+      const uint16_t* pa[LA];
+      const uint16_t* pb[LB];   // KC: fixed row pointers, advanced by k.  NC: unused (rows change with k)
+    };
+    const int lr8 = lane >> 3;
+    auto setup = [&](Loads& L, const TileCoord& t) {
+#pragma unroll
+      for (int i = 0; i < LA; ++i) {
+        const int row = (lw * LA + i) * 8 + lr8;
+        L.pa[i] = p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+      }
+      if constexpr (!P::kBNC) {
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+          const int row = (lw * LB + i) * 8 + lr8;
+          L.pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        }
+      }
+    };
+    // NC: the numbers of the B rows of a k tile.  Where they are plain arithmetic the policy computes them per load
+    // (b_row_ids with a wave-uniform k).  Where they sit in memory (P::kRowIdsInMemory, gathered token rows) lane l
+    // holds the number of the row of k = 64*kt + l, a loader picks its 2 * LB numbers out with v_readlane, and the
+    // numbers travel like the operands: a 4-byte-per-lane global -> LDS load puts the 64 numbers of k tile kt + 3 into a small ring in LDS,
+    // issued before the operand loads of the iteration, so that the partial wait for the next stage also covers it
+    // (the counter retires in issue order); one k tile later they are read back from LDS.  The read-back is an asm
+    // block with its own wait: through a plain load the compiler would first drain every outstanding operand load.
+    struct Rows { int ids; };
+    int* idring = reinterpret_cast<int*>(smem + kOperandLdsBytes / 2) + lw * kIdRingSlots * 64;
+    auto fetch_ids = [&](const TileCoord& t, int kt) {
+      if constexpr (P::kBNC && P::kRowIdsInMemory)
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(p.b_row_id_src(t, kt * kTK) + lane),
+                                         MEFT_LPTR(idring + (kt & (kIdRingSlots - 1)) * 64), 4, 0, 0);
+    };
+    auto rows_for = [&](Rows& R, const TileCoord& t, int kt) {
+      if constexpr (P::kBNC && P::kRowIdsInMemory) {
+        const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(idring + (kt & (kIdRingSlots - 1)) * 64 + lane);
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(R.ids) : "v"(a) : "memory");
+      }
+    };
+    auto issue = [&](const Loads& L, const TileCoord& t, int kt, int stage, const Rows& R) {
+      uint16_t* sa = smem + stage * kStageElems;
+      uint16_t* sb = sa + kTM * kTK;
+#pragma unroll
+      for (int i = 0; i < LA; ++i)
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pa[i] + kt * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
+      if constexpr (!P::kBNC) {
+#pragma unroll
+        for (int i = 0; i < LB; ++i)
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pb[i] + kt * kTK), MEFT_LPTR(sb + (lw * LB + i) * 8 * kTK), 16, 0, 0);
+      } else {
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+          int r0, r1;   // wave-uniform numbers of the two B rows of this load
+          if constexpr (P::kRowIdsInMemory) {
+            r0 = __builtin_amdgcn_readlane(R.ids, 2 * (lw * LB + i));
+            r1 = __builtin_amdgcn_readlane(R.ids, 2 * (lw * LB + i) + 1);
+          } else {
+            const int k0 = kt * kTK + 2 * (lw * LB + i);
+            r0 = p.b_row_ids(t, k0);
+            r1 = p.b_row_ids(t, k0 + 1);
+          }
+          const int krow = 2 * (lw * LB + i) + (lane >> 5);             // this lane's k row inside the tile
+          const int chunk = (lane & 31) ^ (2 * (krow & 7));             // logical 16-byte chunk this lane fetches
+          int col = t.n0 + chunk * 8;
+          col = col > t.Ncols - 8 ? t.Ncols - 8 : col;                  // clamp (columns beyond Ncols are never stored)
+          const uint16_t* src = p.b_row_ptr((lane >> 5) ? r1 : r0) + col;
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (lw * LB + i) * 512), 16, 0, 0);
+        }
+      }
+    };
+
+    // requests the first kStages - 1 k tiles of a tile (and, for row numbers in memory, the numbers of the first
+    // kStages k tiles before them)
+    auto prologue = [&](const Loads& L, const TileCoord& t) {
+      if constexpr (P::kBNC && P::kRowIdsInMemory) {
+#pragma unroll
+        for (int s = 0; s < kStages; ++s) fetch_ids(t, s);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+#pragma unroll
+      for (int s = 0; s < kStages - 1; ++s) {
+        Rows R;
+        rows_for(R, t, s);
+        if (s < t.nk) issue(L, t, s, s, R);
+      }
+    };
+    Loads cur;
+    setup(cur, tc);
+    prologue(cur, tc);
+    for (;;) {
+      const int nk = tc.nk;
+      int stage = 0;
+      bool more = false;
+      TileCoord tn;
+      Loads nxt;
+      for (int kt = 0; kt < nk; ++kt) {
+        // k tile kt has landed once at most LA + LB younger loads of this wave are outstanding (the counter retires
+        // in issue order); with no younger k tile requested, everything is awaited
+        if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        if (kt + kStages - 1 < nk) {
+          int ps = stage - 1;
+          if (ps < 0) ps += kStages;
+          fetch_ids(tc, kt + kStages);                     // row numbers for the request of the next iteration
+          Rows R;
+          rows_for(R, tc, kt + kStages - 1);
+          issue(cur, tc, kt + kStages - 1, ps, R);         // the buffer of k tile kt-1: every compute wave is past it
+        }
+        if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }
+        if (kt == nk - 1 && more) setup(nxt, tn);
+        stage = stage + 1 == kStages ? 0 : stage + 1;
+      }
+      MEFT_BARRIER_LDS();   // every compute wave is done reading operand stages
+      if (more) prologue(nxt, tn);
+      // the epilogue's barriers (two per pass plus those inside the policy's store_rows)
+#pragma unroll
+      for (int b = 0; b < kPasses * (2 + P::kStoreBarriers); ++b) MEFT_BARRIER_LDS();
+      if (!more) return;
+      tc = tn;
+      cur = nxt;
+    }
+  }
+
+  // -------------------------------------------------------------------- compute waves
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
   const int fr = lane & 31, fc = lane >> 5;
   int offA[2], keyA[2];
@@ -190,19 +288,6 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
     }
   }
 
-  int wg = blockIdx.x;
-  TileCoord tc;
-  if (!next_tile(wg, tc)) return;
-  Loads cur;
-  setup(cur, tc);
-  Rows rows;   // row pointers for the next k tile to be requested
-#pragma unroll
-  for (int s = 0; s < kStages - 1; ++s) {
-    rows_for(rows, tc, s);
-    if (s < tc.nk) issue(cur, tc, s, s, rows);
-  }
-  rows_for(rows, tc, kStages - 1);
-
   for (;;) {
     f32x16 acc[2][4];
 #pragma unroll
@@ -216,24 +301,9 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
     int stage = 0;
     bool more = false;
     TileCoord tn;
-    Loads nxt;
     for (int kt = 0; kt < nk; ++kt) {
-      // k tile kt has landed once at most LA + LB younger vector-memory operations are outstanding: the counter
-      // retires loads and stores in issue order (the compiler relies on the same), and everything issued after
-      // k tile kt's loads -- the next k tile's loads, or at kt == 0 also the previous output tile's stores --
-      // is younger.  With a single k tile nothing younger is guaranteed to exist, so everything is awaited.
-      if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-      if (kt + kStages - 1 < nk) {
-        int ps = stage - 1;
-        if (ps < 0) ps += kStages;
-        issue(cur, tc, kt + kStages - 1, ps, rows);  // the buffer of k tile kt-1: every wave is past it (barrier above)
-        rows_for(rows, tc, kt + kStages);                // pointers for the request of the next iteration
-      }
-      // The next tile is located early (scalar loads only) and its row pointers are set up during the last k
-      // tile, when no operand load is outstanding any more, so look-ups with vector loads cost no pipeline drain.
+      MEFT_BARRIER_LDS();   // the loaders have seen k tile kt land
       if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }
-      if (kt == nk - 1 && more) setup(nxt, tn);
       const uint16_t* st = smem + stage * kStageElems;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
@@ -270,16 +340,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
       stage = stage + 1 == kStages ? 0 : stage + 1;
     }
 
-    // every wave is done reading operand stages; ask for the next tile's first stages (0 and 1) right away
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (more) {
-#pragma unroll
-      for (int s = 0; s < kStages - 1; ++s) {
-        rows_for(rows, tn, s);
-        if (s < tn.nk) issue(nxt, tn, s, s, rows);
-      }
-      rows_for(rows, tn, kStages - 1);
-    }
+    MEFT_BARRIER_LDS();   // every compute wave is done reading operand stages; the loaders go on with the next tile
 
     // ---- epilogue: the fp32 tile goes through the LDS region of stage 2, kEpiRows rows at a time, so that the
     // policy can store whole rows with 16-byte accesses.  Layout of a pass: row-major, 256 floats per row, the
@@ -287,7 +348,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
     // write in different banks).  Rows 32*pass .. +31 belong to the waves with wm == 64*(pass/2), fragment pass%2.
     float* tile = reinterpret_cast<float*>(smem + (kStages - 1) * kStageElems);
 #pragma unroll
-    for (int pass = 0; pass < kTM / kEpiRows; ++pass) {
+    for (int pass = 0; pass < kPasses; ++pass) {
       if ((wave >> 1) == (pass >> 1)) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -299,13 +360,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(P p, int n_tiles_boun
           }
         }
       }
-      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-      p.store_rows(tc, pass * kEpiRows, tile, tid);
-      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      MEFT_BARRIER_LDS();
+      p.store_rows(tc, pass * kEpiRows, tile, tid);   // contains P::kStoreBarriers workgroup barriers
+      MEFT_BARRIER_LDS();
     }
     if (!more) break;
     tc = tn;
-    cur = nxt;
   }
 }
 

@@ -134,7 +134,7 @@ struct DispatchWs {
     group_off = c.take<int32_t>((size_t)s.n_blocks + 1);
     tile_off = c.take<int32_t>((size_t)s.n_blocks + 1);
     perm = c.take<int32_t>(n_ent);
-    tok_of_slot = c.take<int32_t>(n_ent);
+    tok_of_slot = c.take<int32_t>(n_ent + kSlotPad);   // padded: see kSlotPad
     slot_of_ent = c.take<int32_t>(n_ent);
     goffp = c.take<int32_t>((size_t)s.n_blocks + 1);
     sched_len = c.take<int32_t>(kXcd);
@@ -406,7 +406,7 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
   // persistent workgroups: one per compute unit (the LDS footprint allows no more), each walking the tile ids
   // wg, wg + 256, ... below `grid`
   const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
-  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(256), kGemmLdsBytes, st, prob, grid);
+  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(kGemmThreads), kGemmLdsBytes, st, prob, grid);
 }
 
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
@@ -416,7 +416,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
   MEFT_LAUNCH("fill_groups", fill_groups_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, n_ent, w.cnt,
               s.n_blocks, BM, w.group_off, w.tile_off, w.perm);
   if (dense) {
-    MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
+    MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + kSlotPad + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
                 s.n_blocks, s.top_e, w.tok_of_slot, w.slot_of_ent, w.goffp);
     MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks,
                 sched_cap(s), w.sched_pairs, w.sched_len);
@@ -571,7 +571,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
 static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& w, const void* h, const void* K,
                         const void* V, const int32_t* S, const int32_t* n_S, hipStream_t st) {
   const size_t n_slots = (size_t)g.nvb * s.T, n_rows = (size_t)g.nvb * g.vbs;
-  const size_t n_thr = n_slots > n_rows ? n_slots : n_rows;
+  const size_t n_thr = (n_slots + kSlotPad) > n_rows ? (n_slots + kSlotPad) : n_rows;
   MEFT_LAUNCH("union_maps", union_maps_kernel, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, n_S, g.cap,
               s.T, g.vbs, g.nvb, w.sblk, w.perm, w.tok_of_slot, w.slot_of_ent, w.group_off, w.goffp, w.rowflag);
   MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, g.nvb, sched_cap(g.vs),

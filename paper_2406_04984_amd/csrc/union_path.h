@@ -6,7 +6,7 @@
 // per-token block-dense path (group = one virtual block with all T tokens), the ReLU being applied in the score
 // GEMM's epilogue instead of a top-k selection.
 #pragma once
-#include "common.h"
+#include "dense_path.h"
 
 namespace meft {
 
@@ -46,6 +46,8 @@ __global__ __launch_bounds__(256) void union_maps_kernel(const int32_t* __restri
       sblk[ent] = -1;
     }
   }
+  // kSlotPad valid entries behind the last real slot (the GEMMs look row numbers up a little beyond a group)
+  if (i >= (long long)n_real * T && i < (long long)n_real * T + kSlotPad) tok_of_slot[i] = 0;
   if (i < (long long)nvb * vbs) rowflag[i] = i < U ? 1 : 0;   // which compacted rows exist
   if (blockIdx.x == 0) {
     const int Tp = (T + 63) & ~63;
