@@ -56,7 +56,7 @@ STAGE_SYMBOL = {
     "router_gemm": "gemm_mfma_kernel<ProbRouter>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<0> >",
     "dact_gemm": "gemm_mfma_kernel<ProbTokKC<1> >", "value_gemm": "gemm_mfma_kernel<ProbTokNC>",
     "dh_gemm": "gemm_mfma_kernel<ProbTokNC>", "dV_gemm": "gemm_mfma_kernel<ProbNeuNC>",
-    "dK_gemm": "gemm_mfma_kernel<ProbNeuNC>", "topk_select": "topk_select_kernel",
+    "dK_gemm": "gemm_mfma_kernel<ProbNeuNC>", "topk_select": "topk_select_reg_kernel<16>",
 }
 
 

@@ -470,9 +470,17 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     const int nb_used = s.n_blocks < n_ent ? s.n_blocks : n_ent;
     launch_gemm_nt(s, a, n_ent / kGemmBM + nb_used, n_ent / kGemmF32BM + nb_used, "score_gemm", st);
   }
-  if (C <= kMaxLdsC)
-    MEFT_LAUNCH("topk_select", topk_select_kernel, dim3(s.T), dim3(256), (size_t)C * 4, st, w.sc, w.sblk, C,
-                s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, dense ? w.Ap : nullptr);
+  if (C <= kMaxLdsC) {
+    // keys in registers, the smallest per-thread count that covers the C candidates with 256 threads
+    uint16_t* ap = dense ? w.Ap : nullptr;
+#define TK(KPT) MEFT_LAUNCH("topk_select", (topk_select_reg_kernel<KPT>), dim3(s.T), dim3(256), 0, st, w.sc, w.sblk, C, s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, ap)
+    if (C <= 256 * 4) TK(4);
+    else if (C <= 256 * 8) TK(8);
+    else if (C <= 256 * 16) TK(16);
+    else if (C <= 256 * 32) TK(32);
+    else TK(48);
+#undef TK
+  }
   else   // candidate sets beyond LDS (e.g. one block holding every neuron): keys stay in global memory
     MEFT_LAUNCH("topk_select_big", topk_select_big_kernel, dim3(s.T), dim3(1024), 0, st, w.sc, w.sblk, C,
                 s.block_size, s.top_e, s.top_k, idx, act);

@@ -146,28 +146,48 @@ __global__ __launch_bounds__(1024) void fill_groups_kernel(const int32_t* __rest
 }
 
 // ---------------------------------------------------------------------------------------------
-// Top-k neurons of one token (Eq. 1 applied to the candidates of the chosen blocks).  One
-// workgroup per token.  The C candidate scores (fp32, candidate position = ascending neuron id)
-// are turned into ordered 32-bit keys in LDS; a most-significant-digit radix select (4 passes of
-// 8 bits) finds the key of the k-th largest and how many of its equals still belong; then one
-// ordered sweep emits the selected positions in ascending order: all keys above the threshold,
-// and the first `need` positions that equal it.  With Ap != nullptr it also writes the token's
+// Top-k neurons of one token (Eq. 1 applied to the candidates of the chosen blocks).  One workgroup per token.
+// The C candidate scores (fp32, candidate position = ascending neuron id) are turned into ordered 32-bit keys; a
+// most-significant-digit radix select (4 passes of 8 bits) finds the key of the k-th largest and how many of its
+// equals still belong; then one ordered sweep emits the selected positions in ascending order: all keys above
+// the threshold, and the first `need` positions that equal it.  With Ap != nullptr it also writes the token's
 // dense activation rows (one per chosen block, slot-major, zero where not selected).
+//
+// The token's keys live in registers: thread `tid` owns the KPT consecutive candidate
+// positions tid*KPT .. tid*KPT + KPT - 1 (256 * KPT >= C), reads them once from global memory and keeps their
+// ordered keys for all four histogram passes, the ordered sweep and the dense activation rows.  LDS only holds
+// the 256-bin histogram; a thread adds runs of equal digits with one atomic, which takes most of the
+// same-address conflicts out of the first pass (sign and exponent bits: a handful of distinct digits).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void topk_select_kernel(const float* __restrict__ sc,
-                                                          const int32_t* __restrict__ sblk, int C, int bs,
-                                                          int e, int k, int32_t* __restrict__ idx,
-                                                          float* __restrict__ act,
-                                                          const int32_t* __restrict__ slot_of_ent, int bsp,
-                                                          uint16_t* __restrict__ Ap) {
-  extern __shared__ uint32_t s_keys[];  // [C]
+template <int KPT>
+__global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __restrict__ sc,
+                                                              const int32_t* __restrict__ sblk, int C, int bs,
+                                                              int e, int k, int32_t* __restrict__ idx,
+                                                              float* __restrict__ act,
+                                                              const int32_t* __restrict__ slot_of_ent, int bsp,
+                                                              uint16_t* __restrict__ Ap) {
   __shared__ int s_hist[256];
   __shared__ int s_w[4];
   __shared__ uint32_t s_prefix;
   __shared__ int s_need;
   const int t = blockIdx.x, tid = threadIdx.x;
   const float* row = sc + (size_t)t * C;
-  for (int i = tid; i < C; i += 256) s_keys[i] = order_key(row[i]);
+  const int p0 = tid * KPT;
+  uint32_t key[KPT];   // 0 for positions beyond C: below every real key, never selected
+  if ((C & 3) == 0 && (KPT & 3) == 0) {
+#pragma unroll
+    for (int z = 0; z < KPT; z += 4) {
+      if (p0 + z < C) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(row + p0 + z);
+        key[z] = order_key(v.x); key[z + 1] = order_key(v.y); key[z + 2] = order_key(v.z); key[z + 3] = order_key(v.w);
+      } else {
+        key[z] = key[z + 1] = key[z + 2] = key[z + 3] = 0u;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int z = 0; z < KPT; ++z) key[z] = p0 + z < C ? order_key(row[p0 + z]) : 0u;
+  }
   if (tid == 0) { s_prefix = 0u; s_need = k; }
   __syncthreads();
 
@@ -176,10 +196,21 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const float* __restric
     __syncthreads();
     const uint32_t prefix = s_prefix;
     const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    for (int i = tid; i < C; i += 256) {
-      const uint32_t key = s_keys[i];
-      if ((key & himask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1);
+    int cur = -1, cnt = 0;
+#pragma unroll
+    for (int z = 0; z < KPT; ++z) {
+      if (p0 + z < C && (key[z] & himask) == prefix) {
+        const int dgt = (int)((key[z] >> shift) & 255u);
+        if (dgt == cur) {
+          ++cnt;
+        } else {
+          if (cnt) atomicAdd(&s_hist[cur], cnt);
+          cur = dgt;
+          cnt = 1;
+        }
+      }
     }
+    if (cnt) atomicAdd(&s_hist[cur], cnt);
     __syncthreads();
     // thread `tid` owns digit 255 - tid, so that an exclusive scan counts the larger digits
     const int digit = 255 - tid;
@@ -197,48 +228,70 @@ __global__ __launch_bounds__(256) void topk_select_kernel(const float* __restric
   const uint32_t thr = s_prefix;
   const int need = s_need;  // how many keys equal to thr are selected (>= 1)
 
-  const int chunk = (C + 255) / 256;
-  const int i0 = tid * chunk, i1 = min(C, i0 + chunk);
   int ngt = 0, neq = 0;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t key = s_keys[i];
-    ngt += key > thr;
-    neq += key == thr;
+#pragma unroll
+  for (int z = 0; z < KPT; ++z) {
+    ngt += key[z] > thr;               // padding keys are 0 <= thr's lower bound: never greater
+    neq += (p0 + z < C) && key[z] == thr;
   }
   int tot;
-  const int packed = block_excl_scan_256(ngt | (neq << 16), s_w, tot);  // C <= 16384 < 2^15
+  const int packed = block_excl_scan_256(ngt | (neq << 16), s_w, tot);  // C <= 12288 < 2^15
   int gt_before = packed & 0xFFFF, eq_before = packed >> 16;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t key = s_keys[i];
-    const bool gt = key > thr, eq = key == thr;
+  uint32_t sel = 0u;   // bit z: position p0 + z is selected (KPT <= 32 bits used per word)
+  uint32_t sel_hi = 0u;
+#pragma unroll
+  for (int z = 0; z < KPT; ++z) {
+    const bool in = p0 + z < C;
+    const bool gt = key[z] > thr, eq = in && key[z] == thr;
     if (gt || (eq && eq_before < need)) {
       const int slot = gt_before + min(eq_before, need);  // selected positions before this one
+      const int i = p0 + z;
       const int q = i / bs, r = i - q * bs;
-      const float v = key_to_float(key);
+      const float v = key_to_float(key[z]);
       idx[(size_t)t * k + slot] = sblk[(size_t)t * e + q] * bs + r;
       act[(size_t)t * k + slot] = v > 0.f ? v : 0.f;
+      if (z < 32) sel |= 1u << z; else sel_hi |= 1u << (z - 32);
     }
-    else if (Ap) s_keys[i] = 0u;  // 0 marks "not selected" for the dense row written below
     gt_before += gt;
     eq_before += eq;
   }
   if (Ap == nullptr) return;
   // dense activation rows A'[slot, 0:bsp] for the matrix-core path: bf16(act) where selected, else 0
-  __syncthreads();
-  for (int q = 0; q < e; ++q) {
-    uint16_t* row = Ap + (size_t)slot_of_ent[t * e + q] * bsp;
-    for (int r = tid * 2; r < bsp; r += 512) {
-      uint32_t w = 0u;
+  uint16_t a16[KPT];
 #pragma unroll
-      for (int z = 0; z < 2; ++z) {
-        if (r + z < bs) {
-          const uint32_t key = s_keys[q * bs + r + z];
-          const float v = key ? key_to_float(key) : 0.f;
-          w |= (v > 0.f ? f32_to_bf16_bits(v) : 0u) << (16 * z);
-        }
+  for (int z = 0; z < KPT; ++z) {
+    const bool on = z < 32 ? ((sel >> z) & 1u) : ((sel_hi >> (z - 32)) & 1u);
+    const float v = on ? key_to_float(key[z]) : 0.f;
+    a16[z] = (uint16_t)(v > 0.f ? f32_to_bf16_bits(v) : 0u);
+  }
+  if (bs % KPT == 0 && (KPT & 7) == 0) {
+    // the thread's positions lie in one block's row, 16-byte aligned
+    if (p0 < C) {
+      const int q = p0 / bs, r0 = p0 - q * bs;
+      uint16_t* dst = Ap + (size_t)slot_of_ent[t * e + q] * bsp + r0;
+#pragma unroll
+      for (int z = 0; z < KPT; z += 8) {
+        u32x4 w;
+        w.x = a16[z] | ((uint32_t)a16[z + 1] << 16); w.y = a16[z + 2] | ((uint32_t)a16[z + 3] << 16);
+        w.z = a16[z + 4] | ((uint32_t)a16[z + 5] << 16); w.w = a16[z + 6] | ((uint32_t)a16[z + 7] << 16);
+        *reinterpret_cast<u32x4*>(dst + z) = w;
       }
-      *reinterpret_cast<uint32_t*>(row + r) = w;
     }
+  } else {
+#pragma unroll
+    for (int z = 0; z < KPT; ++z) {
+      const int i = p0 + z;
+      if (i < C) {
+        const int q = i / bs, r = i - q * bs;
+        Ap[(size_t)slot_of_ent[t * e + q] * bsp + r] = a16[z];
+      }
+    }
+  }
+  // the padding columns bs .. bsp - 1 of the token's rows are zero
+  const int pad = bsp - bs;
+  for (int j = tid; j < e * pad; j += 256) {
+    const int q = j / pad, r = bs + (j - q * pad);
+    Ap[(size_t)slot_of_ent[t * e + q] * bsp + r] = 0;
   }
 }
 
