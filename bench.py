@@ -165,11 +165,12 @@ def main() -> int:
                 "traffic": profiled_traffic(cfg.name, dominant), "avg_launch_ms": round(kern[dominant], 4)}
     if cfg.host_kv:
         # keys/values in pinned host memory: the step is bound by the host link.  Bytes: every block in use of K and
-        # V goes host->device in the forward and again in the backward, the touched rows of dK and dV go back.
+        # V goes host->device in the forward (and again in the backward unless the staged copies are kept), the
+        # touched rows of dK and dV go back.
         torch.cuda.synchronize()
         nt = int(layer.n_touched.item())
         used = int(torch.unique(layer.block_idx).numel())
-        link_bytes = 4.0 * used * cfg.block_size * cfg.d * 2 + 2.0 * nt * cfg.d * 2
+        link_bytes = (2.0 if cfg.keep_staged else 4.0) * used * cfg.block_size * cfg.d * 2 + 2.0 * nt * cfg.d * 2
         gbs = link_bytes / (ms_per_step * 1e-3) / 1e9
         roofline = {"kernel": "host link: hipMemcpyAsync of K, V blocks + rows_to_host", "bound": "host_link",
                     "achieved": round(gbs, 2), "peak": 64.0, "unit": "GB/s", "frac": round(gbs / 64.0, 4),

@@ -70,7 +70,18 @@ typedef enum { MEFT_F32 = 0, MEFT_BF16 = 1 } meft_dtype;
  * creates one side stream, four events and a small pinned buffer on first use and keeps them; two such calls
  * must not be in flight at the same time on different streams.
  */
-enum { MEFT_FLAG_HOST_KV = 1u };
+enum {
+  MEFT_FLAG_HOST_KV = 1u,
+  /*
+   * With MEFT_FLAG_HOST_KV: the device copies of the K and V blocks that meft_sparse_fwd staged in the workspace
+   * are kept for the meft_sparse_bwd of the same step, which then fetches nothing (and does not block the host):
+   * K and V cross the host link once per step, not twice.  This is the one exception to "the workspace carries
+   * nothing from call to call".  The caller promises that the backward uses the same workspace, shape, K and V
+   * as the forward that produced `idx`, on the same stream, with no other call on that workspace in between.
+   * The flag has no effect on the forward.
+   */
+  MEFT_FLAG_KEEP_STAGED = 2u
+};
 
 /*
  * Problem shape.  Requirements (else MEFT_ERR_INVALID_ARG):

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libmeft.so")
 MEFT_OK, MEFT_ERR_INVALID_ARG, MEFT_ERR_UNSUPPORTED, MEFT_ERR_WORKSPACE, MEFT_ERR_DEVICE = range(5)
 MEFT_F32, MEFT_BF16 = 0, 1
 MEFT_FLAG_HOST_KV = 1
+MEFT_FLAG_KEEP_STAGED = 2
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",

@@ -71,7 +71,8 @@ meft_status check_shape(const meft_shape* s) {
   if ((int64_t)s->T * s->top_k >= (1ll << 31) || (int64_t)s->T * C >= (1ll << 31)) return MEFT_ERR_INVALID_ARG;
   if (s->dtype != MEFT_F32 && s->dtype != MEFT_BF16) return MEFT_ERR_INVALID_ARG;
   if (s->activation != 0) return MEFT_ERR_INVALID_ARG;
-  if (s->flags & ~(uint32_t)MEFT_FLAG_HOST_KV) return MEFT_ERR_INVALID_ARG;
+  if (s->flags & ~(uint32_t)(MEFT_FLAG_HOST_KV | MEFT_FLAG_KEEP_STAGED)) return MEFT_ERR_INVALID_ARG;
+  if ((s->flags & MEFT_FLAG_KEEP_STAGED) && !(s->flags & MEFT_FLAG_HOST_KV)) return MEFT_ERR_INVALID_ARG;
   if (s->d % 8 != 0 || s->d > kMaxD || C > kMaxC || s->n_blocks > kMaxBlocks) return MEFT_ERR_UNSUPPORTED;
   return MEFT_OK;
 }
@@ -484,8 +485,9 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
   else   // candidate sets beyond LDS (e.g. one block holding every neuron): keys stay in global memory
     MEFT_LAUNCH("topk_select_big", topk_select_big_kernel, dim3(s.T), dim3(1024), 0, st, w.sc, w.sblk, C,
                 s.block_size, s.top_e, s.top_k, idx, act);
-  if (!out) return launch_status();   // selection only
+  // (also when only the selection is wanted: a backward that reuses the staged copies relies on this wait)
   if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+  if (!out) return launch_status();   // selection only
   if (dense) {
     ProbTokNC pv{};
     pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
@@ -792,6 +794,11 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   // gradient needs it before dh needs K), compute into device staging, then write the touched rows back.
   if (!hostkv_init()) return MEFT_ERR_DEVICE;
   HostKvWs hw(s, ws);
+  if (s.flags & MEFT_FLAG_KEEP_STAGED) {
+    // the forward of this step left the blocks in use in the workspace, and its copies are ordered before
+    // anything enqueued here (the forward made `st` wait for them)
+    rc = bwd_impl(s, h, hw.Kd, hw.Vd, idx, act, dOut, dh, hw.dKd, hw.dVd, touched, n_touched, w, st, nullptr, nullptr);
+  } else {
   if (hipEventRecord(g_hkv.ev_entry, st) != hipSuccess || hipStreamWaitEvent(g_hkv.side, g_hkv.ev_entry, 0) != hipSuccess)
     return MEFT_ERR_DEVICE;
   int32_t* sblk_tmp = hw.pair_blk;
@@ -803,6 +810,7 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   if ((rc = hostkv_fetch(s, cnt_tmp, V, hw.Vd, g_hkv.ev_v, K, hw.Kd, g_hkv.ev_k, st)) != MEFT_OK) return rc;
   rc = bwd_impl(s, h, hw.Kd, hw.Vd, idx, act, dOut, dh, hw.dKd, hw.dVd, touched, n_touched, w, st, g_hkv.ev_k,
                 g_hkv.ev_v);
+  }
   if (rc != MEFT_OK) return rc;
   const int n_rows = s.N < s.T * s.top_k ? s.N : s.T * s.top_k;
   const int vec = s.d * (s.dtype == MEFT_BF16 ? 2 : 4) / 16;

@@ -47,6 +47,7 @@ class Config:
     outlier_scale: float = 1.0
     zipf_s: float = 0.0         # >0: router bias -s*ln(rank), rank a seeded permutation
     host_kv: bool = False       # K, V (and dK, dV) live in pinned host memory
+    keep_staged: bool = False   # with host_kv: the backward reuses the device copies the forward staged
     seed: int = BASE_SEED
 
     @property
@@ -73,7 +74,7 @@ CONFIGS: Dict[str, Config] = {
     "wide_bf16": Config("wide_bf16", "bf16", 4096, 4096, 256, 1024, 8, 512,
                         zipf_s=1.1, seed=BASE_SEED + 4),
     "llama7b_hostkv_bf16": Config("llama7b_hostkv_bf16", "bf16", 8192, 4096, 128, 1024, 4, 256,
-                                  outlier_frac=0.005, outlier_scale=10.0, host_kv=True,
+                                  outlier_frac=0.005, outlier_scale=10.0, host_kv=True, keep_staged=True,
                                   seed=BASE_SEED + 5),
 }
 

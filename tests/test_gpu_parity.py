@@ -110,6 +110,12 @@ def test_keys_and_values_in_pinned_host_memory(P, dtype, d):
     for n in ("block_idx", "idx", "act", "out", "dh", "dK_bits", "dV_bits", "touched"):
         assert (ref[n] == got[n]).all(), n
     assert not ((got["touched"] >= 96) & (got["touched"] < 128)).any()
+    # MEFT_FLAG_KEEP_STAGED: the backward reuses the blocks the forward staged instead of fetching them again
+    tk = synth.Tensors(cfg.replace(host_kv=True, keep_staged=True), t.h, t.Wg, t.K, t.V, t.dOut, t.bias,
+                       t.outlier_channels)
+    kept = P.run_gpu(tk)
+    for n in ("block_idx", "idx", "act", "out", "dh", "dK_bits", "dV_bits", "touched"):
+        assert (ref[n] == kept[n]).all(), n
     from oracle import oracle
     r = oracle.route(t.h, t.Wg, cfg.top_e, t.bias)
     f = oracle.forward(t.h, t.K, t.V, r.block_idx, cfg.block_size, cfg.top_k, want_candidates=True)
