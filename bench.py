@@ -87,6 +87,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--verify", action="store_true", help="check structural invariants of one step first")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements beside the headline metric (optimizer step, batch-union variant); "
+                         "used for kernel profiles of the headline path alone")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the layer shards by token across GPUs only on paper "
@@ -205,7 +208,7 @@ def main() -> int:
     # Outside the headline metric: the optimizer step on the touched rows (row-sparse Adam with fp32 weights and
     # moments), timed per parameter matrix with HIP events; pure HBM traffic, reported against the HBM peak.
     extra = {}
-    if not cfg.host_kv:
+    if not cfg.host_kv and not args.no_extras:
         nt = int(layer.n_touched.item())
         esz = 2 if cfg.dtype == "bf16" else 4
         state = [torch.zeros(cfg.N, cfg.d, device="cuda") for _ in range(2)]
@@ -229,7 +232,7 @@ def main() -> int:
 
     # The batch-union evaluation of Algorithm 1 on the same inputs and selections: every token over all of S.
     ubytes = B.meft_union_workspace_bytes(layer.shape)
-    if ubytes > 0 and not cfg.host_kv:
+    if ubytes > 0 and not cfg.host_kv and not args.no_extras:
         uws = torch.empty((ubytes,), dtype=torch.uint8, device="cuda")
         S = torch.empty_like(layer.touched)
         n_S = torch.zeros_like(layer.n_touched)
