@@ -528,6 +528,16 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
                 touched, n_touched);
     const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
+    // every listed group has the same tiles; in the worst case one XCD holds all groups
+    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
+    const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
+    ProbNeuNC pn{};
+    pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
+    pn.sched = sched; pn.bs = s.block_size; pn.d = s.d;
+    // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
+    // gathers the same dOut rows as the activation-gradient GEMM that follows it
+    pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
+    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<kTokMasked> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
@@ -541,14 +551,6 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
       launch_gemm_mfma("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
-    // every listed group has the same tiles; in the worst case one XCD holds all groups
-    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
-    const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
-    ProbNeuNC pn{};
-    pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
-    pn.sched = sched; pn.bs = s.block_size; pn.d = s.d;
-    pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
-    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
     pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
     launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
     (void)n_ent;
