@@ -56,8 +56,14 @@ STAGE_SYMBOL = {
     "router_gemm": "gemm_mfma_kernel<ProbRouter>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<0> >",
     "dact_gemm": "gemm_mfma_kernel<ProbTokKC<1> >", "value_gemm": "gemm_mfma_kernel<ProbTokNC>",
     "dh_gemm": "gemm_mfma_kernel<ProbTokNC>", "dV_gemm": "gemm_mfma_kernel<ProbNeuNC>",
-    "dK_gemm": "gemm_mfma_kernel<ProbNeuNC>", "topk_select": "topk_select_reg_kernel<16>",
+    "dK_gemm": "gemm_mfma_kernel<ProbNeuNC>", "topk_select": "topk_select_reg_kernel<16>", "reduce_parts": "reduce_parts_kernel<2>",
 }
+
+
+# rows gathered per (token, neuron) pair by the per-pair formulation of a stage (the figure the block-dense kernels
+# are compared against: what they would have to move if no operand were shared between pairs)
+PAIR_ROWS = {"value_gemm": 1, "dact_gemm": 1, "dh_gemm": 1, "dV_gemm": 1, "dK_gemm": 1,
+             "gather_fwd": 1, "gather_bwd": 2, "seg_reduce": 2}
 
 
 def profiled_traffic(workload, stage):
@@ -81,8 +87,8 @@ def profiled_traffic(workload, stage):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="llama7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
@@ -128,6 +134,17 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - w0) * 1e3 / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+
+    # spread of single steps (the same K steps once more, each bracketed by events on the launch stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record()
+        layer.step()
+        b.record()
+    torch.cuda.synchronize()
+    single = sorted(a.elapsed_time(b) for a, b in evs)
+    step_stats = {"median_ms": round(single[len(single) // 2], 4), "min_ms": round(single[0], 4),
+                  "max_ms": round(single[-1], 4)}
 
     # streaming-copy probe: 1 GiB read + 1 GiB written per launch
     probe_bytes = 1 << 30
@@ -188,6 +205,11 @@ def main() -> int:
                 entry["GB/s"] = round(amt / d_s / 1e9, 1)
             else:
                 entry["TFLOP/s"] = round(amt / d_s / 1e12, 2)
+        tr = profiled_traffic(cfg.name, name)
+        if tr is not None:   # HBM bytes of this kernel from the committed rocprofv3 summary
+            entry["hbm_GB/s"] = round((tr["read_bytes"] + tr["written_bytes"]) / (kern[name] * 1e-3) / 1e9, 1)
+        if name in PAIR_ROWS and cfg.dtype == "bf16":   # per-pair bytes (one row of d per gathered matrix and pair)
+            entry["pair_GB/s"] = round(PAIR_ROWS[name] * cfg.T * cfg.top_k * cfg.d * 2 / (kern[name] * 1e-3) / 1e9, 1)
         stages[name] = entry
 
     cpu = None
@@ -259,7 +281,8 @@ def main() -> int:
     line = {
         "metric": "sparse-adapter fwd+bwd tokens/sec per layer",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "single_step": step_stats,
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "N": cfg.N, "n_blocks": cfg.n_blocks,
                    "block_size": cfg.block_size, "top_e": cfg.top_e, "top_k": cfg.top_k,
