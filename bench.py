@@ -252,6 +252,36 @@ def main() -> int:
             extra["adam_rows"] = {"ms_per_matrix": round(ms, 4), "rows": nt, "bytes_per_element": per_elem,
                                   "GB/s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
+    # Host-resident keys and values: three layers' forwards one after the other, then with each layer's transfer
+    # requested before the previous layer's forward is enqueued (the same inputs in every layer, a workspace each).
+    if cfg.host_kv and not args.no_extras:
+        n_layers = 3
+        wss = [layer.ws] + [torch.empty_like(layer.ws) for _ in range(n_layers - 1)]
+        pre = B.make_shape(cfg.T, cfg.d, cfg.n_blocks, cfg.block_size, cfg.top_e, cfg.top_k, cfg.dtype,
+                           flags=B.MEFT_FLAG_HOST_KV | B.MEFT_FLAG_PRESTAGED)
+
+        def fwd_plain(ws):
+            B.meft_sparse_fwd(layer.shape, layer.h, layer.K, layer.V, layer.block_idx, layer.out, layer.idx, layer.act, ws)
+
+        layer.route()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for ws in wss:
+            fwd_plain(ws)
+        torch.cuda.synchronize()
+        seq_ms = (time.perf_counter() - t0) * 1e3 / n_layers
+        t0 = time.perf_counter()
+        B.meft_hostkv_stage(layer.shape, layer.block_idx, layer.K, layer.V, wss[0])
+        for i, ws in enumerate(wss):
+            if i + 1 < n_layers:
+                B.meft_hostkv_stage(layer.shape, layer.block_idx, layer.K, layer.V, wss[i + 1])
+            B.meft_sparse_fwd(pre, layer.h, layer.K, layer.V, layer.block_idx, layer.out, layer.idx, layer.act, ws)
+        torch.cuda.synchronize()
+        pipe_ms = (time.perf_counter() - t0) * 1e3 / n_layers
+        extra["layer_pipeline"] = {"layers": n_layers, "fwd_ms_per_layer_one_after_the_other": round(seq_ms, 3),
+                                   "fwd_ms_per_layer_pipelined": round(pipe_ms, 3)}
+        del wss
+
     # The batch-union evaluation of Algorithm 1 on the same inputs and selections: every token over all of S.
     ubytes = B.meft_union_workspace_bytes(layer.shape)
     if ubytes > 0 and not cfg.host_kv and not args.no_extras:

@@ -80,7 +80,13 @@ enum {
    * as the forward that produced `idx`, on the same stream, with no other call on that workspace in between.
    * The flag has no effect on the forward.
    */
-  MEFT_FLAG_KEEP_STAGED = 2u
+  MEFT_FLAG_KEEP_STAGED = 2u,
+  /*
+   * With MEFT_FLAG_HOST_KV, for meft_sparse_fwd only: the K and V blocks this call needs were already requested
+   * by meft_hostkv_stage on the same workspace with the same block_idx; the forward fetches nothing, does not block
+   * the host, and waits (on the device) for those copies where it needs them.  See meft_hostkv_stage.
+   */
+  MEFT_FLAG_PRESTAGED = 4u
 };
 
 /*
@@ -168,6 +174,24 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
  */
 void meft_profile_enable(int on);
 int meft_profile_read(const char** names, int32_t* launches, float* total_ms, int cap);
+
+/*
+ * Layer pipeline for host-resident keys and values (the paper's Appendix A: retrieval and transfer of one layer's
+ * rows run while the GPU computes, so that the GPU does not wait for them).  The call finds the blocks that
+ * block_idx uses (the host blocks once until the work queued on `stream` so far has produced that list) and
+ * requests their copies from the pinned host matrices K, V into this workspace on the library's side stream; it
+ * returns without waiting for the copies.  A later meft_sparse_fwd with MEFT_FLAG_PRESTAGED on the same workspace
+ * (same shape, block_idx, K, V) then finds them there; one stage call serves one forward.  Calling it for layer l+1 before enqueuing layer l's forward
+ * overlaps l+1's transfer with l's compute; each layer in flight needs a workspace of its own.
+ *   shape     with MEFT_FLAG_HOST_KV set (other flags are ignored)
+ *   block_idx [T, top_e] device, as written by meft_route
+ *   K, V      [N, d] pinned host
+ *   ws        device workspace of meft_workspace_bytes(shape) bytes; the library remembers up to 16 workspaces
+ *             with copies in flight (the oldest is forgotten first)
+ * Errors as for meft_sparse_fwd; MEFT_ERR_INVALID_ARG without MEFT_FLAG_HOST_KV.
+ */
+meft_status meft_hostkv_stage(const meft_shape* shape, const int32_t* block_idx, const void* K, const void* V, void* ws,
+                              size_t ws_bytes, void* stream);
 
 /*
  * Batch-union evaluation: Algorithm 1 as printed gathers the selections of all tokens of the batch into one

@@ -17,11 +17,12 @@ MEFT_OK, MEFT_ERR_INVALID_ARG, MEFT_ERR_UNSUPPORTED, MEFT_ERR_WORKSPACE, MEFT_ER
 MEFT_F32, MEFT_BF16 = 0, 1
 MEFT_FLAG_HOST_KV = 1
 MEFT_FLAG_KEEP_STAGED = 2
+MEFT_FLAG_PRESTAGED = 4
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
            "meft_probe_copy", "meft_adam_rows", "meft_last_device_error",
-           "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd")
+           "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd", "meft_hostkv_stage")
 
 
 class MeftShape(ctypes.Structure):
@@ -75,6 +76,8 @@ _lib.meft_union_fwd.restype = ctypes.c_int
 _lib.meft_union_fwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_union_bwd.restype = ctypes.c_int
 _lib.meft_union_bwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.meft_hostkv_stage.restype = ctypes.c_int
+_lib.meft_hostkv_stage.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_last_device_error.restype = ctypes.c_char_p
 _lib.meft_last_device_error.argtypes = []
 _lib.meft_probe_copy.restype = ctypes.c_int
@@ -155,6 +158,14 @@ def meft_sparse_bwd(shape, h, K, V, idx, act, dOut, dh, dK, dV, touched, n_touch
                               _p(dK), _p(dV), _p(touched), _p(n_touched), wp, wb, _stream(stream))
     if check and rc:
         raise MeftError("meft_sparse_bwd", rc)
+    return rc
+
+
+def meft_hostkv_stage(shape, block_idx, K, V, ws, stream=None, check=True) -> int:
+    wp, wb = _ws(ws)
+    rc = _lib.meft_hostkv_stage(ctypes.byref(shape), _p(block_idx), _p(K), _p(V), wp, wb, _stream(stream))
+    if check and rc:
+        raise MeftError("meft_hostkv_stage", rc)
     return rc
 
 

@@ -71,8 +71,9 @@ meft_status check_shape(const meft_shape* s) {
   if ((int64_t)s->T * s->top_k >= (1ll << 31) || (int64_t)s->T * C >= (1ll << 31)) return MEFT_ERR_INVALID_ARG;
   if (s->dtype != MEFT_F32 && s->dtype != MEFT_BF16) return MEFT_ERR_INVALID_ARG;
   if (s->activation != 0) return MEFT_ERR_INVALID_ARG;
-  if (s->flags & ~(uint32_t)(MEFT_FLAG_HOST_KV | MEFT_FLAG_KEEP_STAGED)) return MEFT_ERR_INVALID_ARG;
-  if ((s->flags & MEFT_FLAG_KEEP_STAGED) && !(s->flags & MEFT_FLAG_HOST_KV)) return MEFT_ERR_INVALID_ARG;
+  if (s->flags & ~(uint32_t)(MEFT_FLAG_HOST_KV | MEFT_FLAG_KEEP_STAGED | MEFT_FLAG_PRESTAGED)) return MEFT_ERR_INVALID_ARG;
+  if ((s->flags & (MEFT_FLAG_KEEP_STAGED | MEFT_FLAG_PRESTAGED)) && !(s->flags & MEFT_FLAG_HOST_KV))
+    return MEFT_ERR_INVALID_ARG;
   if (s->d % 8 != 0 || s->d > kMaxD || C > kMaxC || s->n_blocks > kMaxBlocks) return MEFT_ERR_UNSUPPORTED;
   return MEFT_OK;
 }
@@ -247,6 +248,28 @@ bool hostkv_init() {
     return false;
   g_hkv.ready = true;
   return true;
+}
+
+// Workspaces whose K, V copies were requested ahead of their forward (meft_hostkv_stage), each with the events
+// that follow its K and its V copies.
+struct StageSlot {
+  const void* ws = nullptr;
+  hipEvent_t ev_k = nullptr, ev_v = nullptr;
+};
+constexpr int kStageSlots = 16;
+StageSlot g_slots[kStageSlots];
+int g_slot_next = 0;
+
+StageSlot* stage_slot(const void* ws, bool create) {
+  for (StageSlot& sl : g_slots)
+    if (sl.ws == ws) return &sl;
+  if (!create) return nullptr;
+  StageSlot& sl = g_slots[g_slot_next];
+  g_slot_next = (g_slot_next + 1) % kStageSlots;
+  if (!sl.ev_k && hipEventCreateWithFlags(&sl.ev_k, hipEventDisableTiming) != hipSuccess) return nullptr;
+  if (!sl.ev_v && hipEventCreateWithFlags(&sl.ev_v, hipEventDisableTiming) != hipSuccess) return nullptr;
+  sl.ws = ws;
+  return &sl;
 }
 
 // Reads the per-block entry counts back (the host blocks until the work queued on `st` so far has produced them),
@@ -761,6 +784,12 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   // the dispatch runs, and let the scoring wait for K and the value stage for V.
   if (!hostkv_init()) return MEFT_ERR_DEVICE;
   HostKvWs hw(s, ws);
+  if (s.flags & MEFT_FLAG_PRESTAGED) {   // the copies were requested by meft_hostkv_stage
+    StageSlot* sl = stage_slot(ws, false);
+    if (!sl) return MEFT_ERR_INVALID_ARG;
+    sl->ws = nullptr;   // one stage call serves one forward
+    return fwd_impl(s, h, hw.Kd, hw.Vd, block_idx, out, idx, act, w, st, sl->ev_k, sl->ev_v);
+  }
   if (hipEventRecord(g_hkv.ev_entry, st) != hipSuccess || hipStreamWaitEvent(g_hkv.side, g_hkv.ev_entry, 0) != hipSuccess)
     return MEFT_ERR_DEVICE;   // the device copies may still be read by work queued earlier on this stream
   MEFT_LAUNCH("sort_blocks", sort_blocks_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, block_idx, s.T,
@@ -768,6 +797,30 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, s.T * s.top_e, w.cnt);
   if ((rc = hostkv_fetch(s, w.cnt, K, hw.Kd, g_hkv.ev_k, V, hw.Vd, g_hkv.ev_v, st)) != MEFT_OK) return rc;
   return fwd_impl(s, h, hw.Kd, hw.Vd, block_idx, out, idx, act, w, st, g_hkv.ev_k, g_hkv.ev_v);
+}
+
+meft_status meft_hostkv_stage(const meft_shape* shape, const int32_t* block_idx, const void* K, const void* V, void* ws,
+                              size_t ws_bytes, void* stream) {
+  meft_status rc = check_shape(shape);
+  if (rc != MEFT_OK) return rc;
+  const meft_shape& s = *shape;
+  if (!(s.flags & MEFT_FLAG_HOST_KV) || !block_idx || !K || !V || !aligned16(K) || !aligned16(V)) return MEFT_ERR_INVALID_ARG;
+  FwdWs w(s, ws);
+  if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
+  if (s.T == 0) return MEFT_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  clear_stale_error();
+  if (!hostkv_init()) return MEFT_ERR_DEVICE;
+  HostKvWs hw(s, ws);
+  StageSlot* sl = stage_slot(ws, true);
+  if (!sl) return MEFT_ERR_DEVICE;
+  if (hipEventRecord(g_hkv.ev_entry, st) != hipSuccess || hipStreamWaitEvent(g_hkv.side, g_hkv.ev_entry, 0) != hipSuccess)
+    return MEFT_ERR_DEVICE;   // the device copies may still be read by work queued earlier on this stream
+  MEFT_LAUNCH("sort_blocks", sort_blocks_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, block_idx, s.T,
+              s.top_e, s.n_blocks, w.sblk);
+  MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, s.T * s.top_e, w.cnt);
+  if ((rc = hostkv_fetch(s, w.cnt, K, hw.Kd, sl->ev_k, V, hw.Vd, sl->ev_v, st)) != MEFT_OK) return rc;
+  return launch_status();
 }
 
 meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* K, const void* V,

@@ -94,7 +94,11 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(B):
     host_kv = _shape(B, flags=B.MEFT_FLAG_HOST_KV)
     assert B.meft_check_shape(host_kv) == B.MEFT_OK
     assert B.meft_check_shape(_shape(B, flags=B.MEFT_FLAG_HOST_KV | B.MEFT_FLAG_KEEP_STAGED)) == B.MEFT_OK
-    assert B.meft_check_shape(_shape(B, flags=4)) == B.MEFT_ERR_INVALID_ARG
+    assert B.meft_check_shape(_shape(B, flags=4)) == B.MEFT_ERR_INVALID_ARG       # needs MEFT_FLAG_HOST_KV
+    assert B.meft_check_shape(_shape(B, flags=7)) == B.MEFT_OK
+    assert B.meft_check_shape(_shape(B, flags=9)) == B.MEFT_ERR_INVALID_ARG
+    fake = 0x1000
+    assert B._lib.meft_hostkv_stage(ctypes.byref(_shape(B)), fake, fake, fake, fake, 1 << 30, None) == B.MEFT_ERR_INVALID_ARG
     # the host-resident variant needs room for device copies of K, V and staging for dK, dV
     assert B.meft_workspace_bytes(host_kv) >= B.meft_workspace_bytes(s) + 4 * 32 * 64 * 4
 
