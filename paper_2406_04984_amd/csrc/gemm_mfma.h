@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
         __builtin_amdgcn_global_load_lds(MEFT_GPTR(p.b_row_id_src(t, kt * kTK) + lane),
                                          MEFT_LPTR(idring + (kt & (kIdRingSlots - 1)) * 64), 4, 0, 0);
     };
-    auto rows_for = [&](Rows& R, const TileCoord& t, int kt) {
+    auto rows_for = [&](Rows& R, int kt) {   // the numbers of k tile kt, out of the ring
       if constexpr (P::kBNC && P::kRowIdsInMemory) {
         const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(idring + (kt & (kIdRingSlots - 1)) * 64 + lane);
         asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(R.ids) : "v"(a) : "memory");
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
 #pragma unroll
       for (int s = 0; s < kStages - 1; ++s) {
         Rows R;
-        rows_for(R, t, s);
+        rows_for(R, s);
         if (s < t.nk) issue(L, t, s, s, R);
       }
     };
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
           if (ps < 0) ps += kStages;
           fetch_ids(tc, kt + kStages);                     // row numbers for the request of the next iteration
           Rows R;
-          rows_for(R, tc, kt + kStages - 1);
+          rows_for(R, kt + kStages - 1);
           issue(cur, tc, kt + kStages - 1, ps, R);         // the buffer of k tile kt-1: every compute wave is past it
         }
         if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }

@@ -447,7 +447,6 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
   }
 }
 
-template <int NVDUMMY = 0>
 void launch_reduce_parts(const meft_shape& s, const uint16_t* part, const DispatchWs& w, void* out, hipStream_t st) {
   int nthr, nv;
   row_launch(s.d, nthr, nv);
@@ -533,7 +532,6 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
   const int P = s.T * s.top_k;
 
   if (use_dense(s)) {
-    const int n_ent = s.T * s.top_e;
     const int bsp = round64(s.block_size);
     const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
                    *vv = static_cast<const uint16_t*>(V), *gg = static_cast<const uint16_t*>(dOut);
@@ -576,7 +574,6 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     }
     pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
     launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
-    (void)n_ent;
     return launch_status();
   }
 
