@@ -504,9 +504,17 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     else TK(48);
 #undef TK
   }
-  else   // candidate sets beyond LDS (e.g. one block holding every neuron): keys stay in global memory
+  else if (C <= 1024 * 64) {
+    // e.g. one block holding every neuron: 1024 threads per token, still with the keys in registers
+#define TK(KPT) MEFT_LAUNCH("topk_select_big", (topk_select_reg1024_kernel<KPT>), dim3(s.T), dim3(1024), 0, st, w.sc, w.sblk, C, s.block_size, s.top_e, s.top_k, idx, act)
+    if (C <= 1024 * 16) TK(16);
+    else if (C <= 1024 * 32) TK(32);
+    else TK(64);
+#undef TK
+  } else {   // beyond that the keys stay in global memory and are read once per pass
     MEFT_LAUNCH("topk_select_big", topk_select_big_kernel, dim3(s.T), dim3(1024), 0, st, w.sc, w.sblk, C,
                 s.block_size, s.top_e, s.top_k, idx, act);
+  }
   // (also when only the selection is wanted: a backward that reuses the staged copies relies on this wait)
   if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
   if (!out) return launch_status();   // selection only

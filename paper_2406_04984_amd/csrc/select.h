@@ -296,6 +296,106 @@ __global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __res
 }
 
 // ---------------------------------------------------------------------------------------------
+// The register-resident selection for 12288 < C <= 65536 candidates: 1024 threads per token, thread `tid` owns
+// the KPT consecutive positions from tid*KPT (1024 * KPT >= C).  Same passes as above; no dense activation rows
+// (shapes this large do not take the matrix-core path).
+// ---------------------------------------------------------------------------------------------
+template <int KPT>
+__global__ __launch_bounds__(1024) void topk_select_reg1024_kernel(const float* __restrict__ sc,
+                                                                   const int32_t* __restrict__ sblk, int C, int bs,
+                                                                   int e, int k, int32_t* __restrict__ idx,
+                                                                   float* __restrict__ act) {
+  __shared__ int s_hist[256];
+  __shared__ int s_w[16];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const float* row = sc + (size_t)t * C;
+  const int p0 = tid * KPT;
+  // 0 for positions beyond C: below every key of a finite score (whose top byte is never 0), so it is never
+  // selected, never equals the threshold, and is only ever counted in digit 0 of the first pass, which the search
+  // for the k-th largest (k <= C) does not reach
+  uint32_t key[KPT];
+  if ((C & 3) == 0) {
+#pragma unroll
+    for (int z = 0; z < KPT; z += 4) {
+      if (p0 + z < C) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(row + p0 + z);
+        key[z] = order_key(v.x); key[z + 1] = order_key(v.y); key[z + 2] = order_key(v.z); key[z + 3] = order_key(v.w);
+      } else {
+        key[z] = key[z + 1] = key[z + 2] = key[z + 3] = 0u;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int z = 0; z < KPT; ++z) key[z] = p0 + z < C ? order_key(row[p0 + z]) : 0u;
+  }
+  if (tid == 0) { s_prefix = 0u; s_need = k; }
+  __syncthreads();
+
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) s_hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    int cur = -1, cnt = 0;
+#pragma unroll
+    for (int z = 0; z < KPT; ++z) {
+      if ((key[z] & himask) == prefix) {   // padding keys (0) only ever land in digit 0 of the first pass
+        const int dgt = (int)((key[z] >> shift) & 255u);
+        if (dgt == cur) {
+          ++cnt;
+        } else {
+          if (cnt) atomicAdd(&s_hist[cur], cnt);
+          cur = dgt;
+          cnt = 1;
+        }
+      }
+    }
+    if (cnt) atomicAdd(&s_hist[cur], cnt);
+    __syncthreads();
+    // thread `tid` < 256 owns digit 255 - tid, so that an exclusive scan counts the larger digits
+    const int digit = 255 - tid;
+    const int h = tid < 256 ? s_hist[digit] : 0;
+    int tot;
+    const int above = block_excl_scan_1024(h, s_w, tot);
+    const int need = s_need;
+    __syncthreads();
+    if (tid < 256 && above < need && need <= above + h) {
+      s_prefix = prefix | ((uint32_t)digit << shift);
+      s_need = need - above;
+    }
+    __syncthreads();
+  }
+  const uint32_t thr = s_prefix;
+  const int need = s_need;  // how many keys equal to thr are selected (>= 1)
+
+  int ngt = 0, neq = 0;
+#pragma unroll
+  for (int z = 0; z < KPT; ++z) {
+    ngt += key[z] > thr;
+    neq += key[z] == thr;
+  }
+  int tot;
+  int gt_before = block_excl_scan_1024(ngt, s_w, tot);
+  int eq_before = block_excl_scan_1024(neq, s_w, tot);
+#pragma unroll
+  for (int z = 0; z < KPT; ++z) {
+    const bool gt = key[z] > thr, eq = key[z] == thr;
+    if (gt || (eq && eq_before < need)) {
+      const int slot = gt_before + min(eq_before, need);  // selected positions before this one
+      const int i = p0 + z;
+      const int q = i / bs, r = i - q * bs;
+      const float v = key_to_float(key[z]);
+      idx[(size_t)t * k + slot] = sblk[(size_t)t * e + q] * bs + r;
+      act[(size_t)t * k + slot] = v > 0.f ? v : 0.f;
+    }
+    gt_before += gt;
+    eq_before += eq;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // The same selection for candidate sets that do not fit in LDS (the paper's ablation without key experts
 // is one block holding every neuron: Section 4.3 "MEFT w/o KE", Eq. 1-4 over all r neurons).  The scores
 // stay in global memory and are read once per pass: four histogram passes (8 bits each) for the k-th
