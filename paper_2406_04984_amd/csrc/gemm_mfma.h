@@ -409,33 +409,27 @@ __global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __rest
       s_sorted[rank] = rows;
     }
     __syncthreads();
-    if (tid == 0) {
-      int load[kXcd], n[kXcd], tiles[kXcd];
-#pragma unroll
-      for (int x = 0; x < kXcd; ++x) { load[x] = 0; n[x] = 0; tiles[x] = 0; }
+    if (tid < 64) {
+      // the deal itself is sequential; lanes 0..7 of the first wave each keep one XCD's work, list length and tile
+      // count, and a three-step DPP butterfly finds the least loaded XCD (ties to the lower one)
+      const int lane = tid;
+      int load = 0, n = 0, tiles = 0;
       for (int i = 0; i < n_full; ++i) {   // descending order: the non-empty groups come first
         const int g = s_order[i], r = s_sorted[i];
-        int best = 0, least = load[0];   // no run-time array index: the counters stay in registers
-#pragma unroll
-        for (int x = 1; x < kXcd; ++x) {
-          const bool lt = load[x] < least;
-          best = lt ? x : best;
-          least = lt ? load[x] : least;
-        }
-#pragma unroll
-        for (int x = 0; x < kXcd; ++x) {   // constant indices keep the counters in registers
-          if (x == best) {
-            grp[(size_t)x * cap + n[x]] = make_int2(g, tiles[x]);
-            n[x] += 1;
-            tiles[x] += (r + kTM - 1) / kTM;
-            load[x] += (r + 63) / 64 + 2;
-          }
+        int key = lane < kXcd ? ((load << 3) | lane) : 0x7FFFFFFF;
+        key = min(key, __builtin_amdgcn_update_dpp(key, key, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+        key = min(key, __builtin_amdgcn_update_dpp(key, key, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+        key = min(key, __builtin_amdgcn_update_dpp(key, key, 0x141, 0xF, 0xF, false));   // row_half_mirror
+        if (lane == (key & (kXcd - 1))) {   // true in one of the lanes 0..7 only: the higher lanes hold 0x7FFFFFFF
+          grp[(size_t)lane * cap + n] = make_int2(g, tiles);
+          n += 1;
+          tiles += (r + kTM - 1) / kTM;
+          load += (r + 63) / 64 + 2;
         }
       }
-#pragma unroll
-      for (int x = 0; x < kXcd; ++x) {
-        grp[(size_t)x * cap + n[x]] = make_int2(-1, tiles[x]);
-        len[x] = n[x];
+      if (lane < kXcd) {
+        grp[(size_t)lane * cap + n] = make_int2(-1, tiles);
+        len[lane] = n;
       }
     }
   } else if (tid < kXcd) {
