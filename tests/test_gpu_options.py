@@ -1,0 +1,95 @@
+"""The optional arguments and the calling conventions of the three main entry points, on both formulations
+(per-pair gather: f32, block-dense matrix-core: bf16): nullable outputs, a workspace full of garbage, a caller's
+stream, one workspace shared by different shapes.  Everything is compared bit for bit with a plain run."""
+import numpy as np
+import pytest
+
+from paper_2406_04984_amd import synth
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+CASES = [dict(T=150, d=72, n_blocks=6, block_size=40, top_e=2, top_k=12, dtype="f32", seed=1101),
+         dict(T=300, d=192, n_blocks=7, block_size=72, top_e=3, top_k=30, dtype="bf16", seed=1102)]
+NAMES = ("block_idx", "block_score", "idx", "act", "out", "dh", "dK_bits", "dV_bits", "touched")
+
+
+def _same(a, b, names=NAMES):
+    for n in names:
+        assert np.array_equal(a[n], b[n]), n
+
+
+@pytest.mark.parametrize("kw", CASES, ids=["gather_f32", "dense_bf16"])
+def test_workspace_contents_do_not_matter(kw):
+    import torch
+    t = synth.make_inputs(synth.small_case(**kw))
+    ref = P.run_gpu(t)
+    layer = P.DeviceLayer(t)
+    layer.fill_grad_sentinel()
+    for call in (layer.route, layer.fwd, layer.bwd):
+        layer.ws.fill_(0xFF)          # NaN patterns and negative integers everywhere
+        call()
+    _same(ref, layer.results())
+    for call in (layer.route, layer.fwd, layer.bwd):
+        layer.ws.fill_(0x00)
+        call()
+    _same(ref, layer.results())
+
+
+@pytest.mark.parametrize("kw", CASES, ids=["gather_f32", "dense_bf16"])
+def test_nullable_outputs(kw):
+    import torch
+    t = synth.make_inputs(synth.small_case(**kw))
+    ref = P.run_gpu(t)
+    layer = P.DeviceLayer(t)
+    layer.fill_grad_sentinel()
+    B = layer.B
+    B.meft_route(layer.shape, layer.h, layer.Wg, layer.bias, layer.block_idx, None, layer.ws)   # no block scores
+    layer.fwd()
+    layer.dh.fill_(7.0)
+    layer.bwd(want_dh=False)                                                                     # no dh
+    got = layer.results()
+    _same(ref, got, [n for n in NAMES if n not in ("block_score", "dh")])
+    assert bool((layer.dh == 7.0).all()), "dh was written although it was not asked for"
+
+
+@pytest.mark.parametrize("kw", CASES, ids=["gather_f32", "dense_bf16"])
+def test_on_a_stream_of_the_caller(kw):
+    import torch
+    t = synth.make_inputs(synth.small_case(**kw))
+    ref = P.run_gpu(t)
+    layer = P.DeviceLayer(t)
+    layer.fill_grad_sentinel()
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):       # the binding passes torch's current stream
+        layer.step()
+    st.synchronize()
+    _same(ref, layer.results())
+
+
+def test_one_workspace_for_different_shapes():
+    import torch
+    ts = [synth.make_inputs(synth.small_case(**kw)) for kw in CASES]
+    refs = [P.run_gpu(t) for t in ts]
+    layers = [P.DeviceLayer(t) for t in ts]
+    big = max(layers, key=lambda la: la.ws.numel()).ws
+    for la in layers:
+        la.ws = big
+        la.fill_grad_sentinel()
+    for _ in range(2):
+        for la, ref in zip(layers, refs):
+            la.step()
+            _same(ref, la.results())
+
+
+def test_everything_selected_on_the_matrix_core_path():
+    """top_e = n_blocks, top_k = N in bf16: the block-dense kernels compute the dense parallel adapter (Section 2)."""
+    from oracle import dense_ref
+    cfg = synth.small_case(T=90, d=128, n_blocks=4, block_size=32, top_e=4, top_k=128, dtype="bf16", seed=1103)
+    t = synth.make_inputs(cfg)
+    g = P.run_gpu(t)
+    assert (g["idx"] == np.arange(cfg.N)[None, :]).all()
+    assert P.rel_l2(g["out"], dense_ref.dense_adapter(t.h, t.K, t.V)) <= 2e-2
+    dh, dK, dV = dense_ref.dense_adapter_grads(t.h, t.K, t.V, t.dOut)
+    assert P.rel_l2(g["dh"], dh) <= 2e-2 and P.rel_l2(g["dK"], dK) <= 2e-2 and P.rel_l2(g["dV"], dV) <= 2e-2
