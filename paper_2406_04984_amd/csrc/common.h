@@ -26,6 +26,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return u >> 16;
 }
 
+// two floats -> two bf16 in one word (lo in bits 0..15), round to nearest even: one v_cvt_pk_bf16_f32 on gfx950
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_hw;
+typedef __attribute__((ext_vector_type(2))) float f32x2_hw;
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_hw v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
+}
+
 // Eight consecutive elements of a row as floats.  Rows are 16-byte aligned and d % 8 == 0.
 template <typename T>
 struct Vec8;
@@ -59,10 +67,10 @@ struct Vec8<bf16_t> {
   }
   static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
     u32x4 a;
-    a.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-    a.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
-    a.z = f32_to_bf16_bits(v[4]) | (f32_to_bf16_bits(v[5]) << 16);
-    a.w = f32_to_bf16_bits(v[6]) | (f32_to_bf16_bits(v[7]) << 16);
+    a.x = pack_bf16x2(v[0], v[1]);
+    a.y = pack_bf16x2(v[2], v[3]);
+    a.z = pack_bf16x2(v[4], v[5]);
+    a.w = pack_bf16x2(v[6], v[7]);
     *reinterpret_cast<u32x4*>(p) = a;
   }
 };

@@ -190,6 +190,8 @@ struct ProbTokNC {
   }
   __device__ int b_row_ids(const TileCoord& tc, int k) const { return tc.g * bs + (k < bs ? k : bs - 1); }
   __device__ const uint16_t* b_row_ptr(int row) const { return W + (size_t)row * d; }
+  __device__ uint16_t* out_base(const TileCoord& tc) const { return part + (size_t)tc.slot0 * d; }
+  __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < tc.Mrows; }
   __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
     const int c = (tid & 31) * 8, n = tc.n0 + c;
     if (n >= d) return;   // d % 64 == 0: a group of 8 columns is fully in or out
@@ -238,6 +240,8 @@ struct ProbNeuNC {
   // tok_of_slot is padded by kSlotPad valid entries, which covers k0 + 63 up to the padded contraction length + 127
   __device__ const int32_t* b_row_id_src(const TileCoord& tc, int k0) const { return tok_of_slot + tc.slot0 + k0; }
   __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }
+  __device__ uint16_t* out_base(const TileCoord& tc) const { return G + (size_t)tc.g * bs * d; }
+  __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < bs && flag[(size_t)tc.g * bs + m] > 0; }
   __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
     // a wave stores two rows per step (32 lanes x 8 columns each); their touched flags are wave-uniform and
     // read through the constant address space (scalar loads)
