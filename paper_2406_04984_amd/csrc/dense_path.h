@@ -172,7 +172,6 @@ struct ProbTokKC {
 struct ProbTokNC {
   static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = false;
-  static constexpr int kStoreBarriers = 0;
   const uint16_t* A;          // A' or DS'
   const uint16_t* W;          // V or K, [N, d]
   const int32_t* group_off;
@@ -192,20 +191,6 @@ struct ProbTokNC {
   __device__ const uint16_t* b_row_ptr(int row) const { return W + (size_t)row * d; }
   __device__ uint16_t* out_base(const TileCoord& tc) const { return part + (size_t)tc.slot0 * d; }
   __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < tc.Mrows; }
-  __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
-    const int c = (tid & 31) * 8, n = tc.n0 + c;
-    if (n >= d) return;   // d % 64 == 0: a group of 8 columns is fully in or out
-#pragma unroll
-    for (int it = 0; it < kEpiRows / 8; ++it) {
-      const int r = (tid >> 5) + it * 8;
-      const int m = tc.m0 + r0 + r;
-      if (m >= tc.Mrows) break;
-      const f32x4 a = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
-      const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
-      const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-      Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(part) + (size_t)(tc.slot0 + m) * d + n, x);
-    }
-  }
 };
 
 // Neuron-major, B contiguous along n: G_b[bs, d] = AT_b[bs, slots] . X[token(slot), :]
@@ -213,7 +198,6 @@ struct ProbTokNC {
 struct ProbNeuNC {
   static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = true;
-  static constexpr int kStoreBarriers = 0;
   const uint16_t* AT;         // per group [bs, Mgp] at element offset goffp[g]*bs
   const uint16_t* X;          // [T, d]
   const int32_t* group_off; const int32_t* goffp; const int32_t* tok_of_slot;
@@ -242,29 +226,6 @@ struct ProbNeuNC {
   __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }
   __device__ uint16_t* out_base(const TileCoord& tc) const { return G + (size_t)tc.g * bs * d; }
   __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < bs && flag[(size_t)tc.g * bs + m] > 0; }
-  __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
-    // a wave stores two rows per step (32 lanes x 8 columns each); their touched flags are wave-uniform and
-    // read through the constant address space (scalar loads)
-    const auto* cflag = as_const(flag);
-    const int c = (tid & 31) * 8, n = tc.n0 + c;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int hi = (tid >> 5) & 1;
-#pragma unroll
-    for (int it = 0; it < kEpiRows / 8; ++it) {
-      const int re = 2 * w + it * 8;                  // even row of this wave's pair
-      const int me = tc.m0 + r0 + re;
-      if (me >= bs) break;
-      const size_t je = (size_t)tc.g * bs + me;
-      const int f0 = cflag[je];
-      const int f1 = (me + 1 < bs) ? cflag[je + 1] : 0;
-      const int r = re + hi;
-      if ((hi ? f1 : f0) <= 0 || n >= d) continue;
-      const f32x4 a = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
-      const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
-      const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-      Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(G) + (je + hi) * d + n, x);
-    }
-  }
 };
 
 // ---- helper kernels ----------------------------------------------------------------------------

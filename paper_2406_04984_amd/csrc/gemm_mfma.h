@@ -5,11 +5,13 @@
 // A is always contiguous along k.  B is either contiguous along k ("KC": rows indexed by n, used for
 // the router and key scores, Eq. 5 / Eq. 6, and for dOut.V^T in the backward) or contiguous along n
 // ("NC": rows indexed by k, used where the contraction runs over neurons or tokens: the value sum of
-// Eq. 4, dh, dK, dV).
+// Eq. 4, dh, dK, dV).  This file holds what both layouts share and the kernel of the KC problems, whose
+// outputs need a pass through LDS (fp32 scores scattered by entry, masked activations in two layouts);
+// gemm_stream.h holds the kernel of the NC problems.
 //
-// Tile 128 (m) x 256 (n) x 64 (k), 4 waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles.
-// Operands go global -> LDS directly (global_load_lds, 16 B per lane), three stages of 48 KB in a
-// ring with one barrier per k tile; the wait for a stage is a partial vmcnt so that the next
+// Tile 128 (m) x 256 (n) x 64 (k), 4 compute waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles, plus
+// loader waves.  Operands go global -> LDS directly (global_load_lds, 16 B per lane), three stages of
+// 48 KB in a ring with one barrier per k tile; the wait for a stage is a partial vmcnt so that the next
 // stage's loads stay in flight.  LDS layouts are XOR-swizzled so that both the linear DMA writes
 // and the fragment reads are free of bank conflicts:
 //   k-contiguous operand: rows of 64 k = 8 chunks of 16 B; logical chunk c of row r sits at chunk
@@ -62,17 +64,12 @@ struct TileCoord {
 //   __device__ bool locate(int wg, TileCoord&) const;   false: no tile with id wg, nor with any larger id on
 //                                                       the same XCD (ids wg + 8, wg + 16, ...)
 //   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
-//   KC: __device__ const uint16_t* b_row(const TileCoord&, int n) const;   start of B row n (clamped)
-//   static constexpr bool kRowIdsInMemory;              (false for KC)  For NC:
-//       false: __device__ int b_row_ids(const TileCoord&, int k) const;  number of the B row that holds k (plain
-//              arithmetic, no memory access), any valid row for k beyond the contraction length;
-//       true:  __device__ const int32_t* b_row_id_src(const TileCoord&, int k0) const;  where the numbers of the B rows
-//              of k0 .. k0 + 63 are stored (valid rows also beyond the contraction length: those products are zero);
-//              called for k0 up to max(nk, kStages - 1) * 64;  and
-//       __device__ const uint16_t* b_row_ptr(int row) const;      its start
+// and, for the kernel in this file (KC):
+//   __device__ const uint16_t* b_row(const TileCoord&, int n) const;   start of B row n (clamped)
 //   __device__ void store_rows(const TileCoord&, int r0, float* rows, int tid) const;   write tile rows r0..r0+31;
 //       executed by the 256 compute threads (tid 0..255); any workgroup barrier inside must be MEFT_BARRIER_LDS()
 //   static constexpr int kStoreBarriers;                number of such barriers in one store_rows call
+// (gemm_stream.h lists what an NC policy provides instead.)
 //
 // acc[i][j][r] of a wave holds C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,
 // n = wn + j*32 + lane%32 (tile-local); the kernel lays 32 rows at a time out row-major in LDS (tile_index with
@@ -124,6 +121,7 @@ constexpr int kGemmThreads = 256 + 64 * kLoaders;
 // requested before the epilogue of the current one.
 template <class P>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
+  static_assert(!P::kBNC, "n-contiguous B operands go through gemm_stream_kernel");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -139,11 +137,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
     // ------------------------------------------------------------------ loader waves
     const int lw = wave - 4;
     constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (8 rows x 128 B) per loader and stage: 8
-    constexpr int LB = 32 / kLoaders;        // B wave-loads per loader and stage (KC: 8 rows x 128 B; NC: 2 rows x 512 B): 16
+    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (8 rows x 128 B) per loader and stage: 16
     static_assert(LA + LB <= 63, "partial vmcnt wait out of range");
     struct Loads {
       const uint16_t* pa[LA];
-      const uint16_t* pb[LB];   // KC: fixed row pointers, advanced by k.  NC: unused (rows change with k)
+      const uint16_t* pb[LB];
     };
     const int lr8 = lane >> 3;
     auto setup = [&](Loads& L, const TileCoord& t) {
@@ -152,80 +150,28 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
         const int row = (lw * LA + i) * 8 + lr8;
         L.pa[i] = p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
       }
-      if constexpr (!P::kBNC) {
 #pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          const int row = (lw * LB + i) * 8 + lr8;
-          L.pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
-        }
+      for (int i = 0; i < LB; ++i) {
+        const int row = (lw * LB + i) * 8 + lr8;
+        L.pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
       }
     };
-    // NC: the numbers of the B rows of a k tile.  Where they are plain arithmetic the policy computes them per load
-    // (b_row_ids with a wave-uniform k).  Where they sit in memory (P::kRowIdsInMemory, gathered token rows) lane l
-    // holds the number of the row of k = 64*kt + l, a loader picks its 2 * LB numbers out with v_readlane, and the
-    // numbers travel like the operands: a 4-byte-per-lane global -> LDS load puts the 64 numbers of k tile kt + 3 into a small ring in LDS,
-    // issued before the operand loads of the iteration, so that the partial wait for the next stage also covers it
-    // (the counter retires in issue order); one k tile later they are read back from LDS.  The read-back is an asm
-    // block with its own wait: through a plain load the compiler would first drain every outstanding operand load.
-    struct Rows { int ids; };
-    int* idring = reinterpret_cast<int*>(smem + kOperandLdsBytes / 2) + lw * kIdRingSlots * 64;
-    auto fetch_ids = [&](const TileCoord& t, int kt) {
-      if constexpr (P::kBNC && P::kRowIdsInMemory)
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(p.b_row_id_src(t, kt * kTK) + lane),
-                                         MEFT_LPTR(idring + (kt & (kIdRingSlots - 1)) * 64), 4, 0, 0);
-    };
-    auto rows_for = [&](Rows& R, int kt) {   // the numbers of k tile kt, out of the ring
-      if constexpr (P::kBNC && P::kRowIdsInMemory) {
-        const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(idring + (kt & (kIdRingSlots - 1)) * 64 + lane);
-        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(R.ids) : "v"(a) : "memory");
-      }
-    };
-    auto issue = [&](const Loads& L, const TileCoord& t, int kt, int stage, const Rows& R) {
+    auto issue = [&](const Loads& L, int kt, int stage) {
       uint16_t* sa = smem + stage * kStageElems;
       uint16_t* sb = sa + kTM * kTK;
 #pragma unroll
       for (int i = 0; i < LA; ++i)
         __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pa[i] + kt * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
-      if constexpr (!P::kBNC) {
 #pragma unroll
-        for (int i = 0; i < LB; ++i)
-          __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pb[i] + kt * kTK), MEFT_LPTR(sb + (lw * LB + i) * 8 * kTK), 16, 0, 0);
-      } else {
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          int r0, r1;   // wave-uniform numbers of the two B rows of this load
-          if constexpr (P::kRowIdsInMemory) {
-            r0 = __builtin_amdgcn_readlane(R.ids, 2 * (lw * LB + i));
-            r1 = __builtin_amdgcn_readlane(R.ids, 2 * (lw * LB + i) + 1);
-          } else {
-            const int k0 = kt * kTK + 2 * (lw * LB + i);
-            r0 = p.b_row_ids(t, k0);
-            r1 = p.b_row_ids(t, k0 + 1);
-          }
-          const int krow = 2 * (lw * LB + i) + (lane >> 5);             // this lane's k row inside the tile
-          const int chunk = (lane & 31) ^ (2 * (krow & 7));             // logical 16-byte chunk this lane fetches
-          int col = t.n0 + chunk * 8;
-          col = col > t.Ncols - 8 ? t.Ncols - 8 : col;                  // clamp (columns beyond Ncols are never stored)
-          const uint16_t* src = p.b_row_ptr((lane >> 5) ? r1 : r0) + col;
-          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (lw * LB + i) * 512), 16, 0, 0);
-        }
-      }
+      for (int i = 0; i < LB; ++i)
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pb[i] + kt * kTK), MEFT_LPTR(sb + (lw * LB + i) * 8 * kTK), 16, 0, 0);
     };
 
-    // requests the first kStages - 1 k tiles of a tile (and, for row numbers in memory, the numbers of the first
-    // kStages k tiles before them)
+    // requests the first kStages - 1 k tiles of a tile
     auto prologue = [&](const Loads& L, const TileCoord& t) {
-      if constexpr (P::kBNC && P::kRowIdsInMemory) {
 #pragma unroll
-        for (int s = 0; s < kStages; ++s) fetch_ids(t, s);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      }
-#pragma unroll
-      for (int s = 0; s < kStages - 1; ++s) {
-        Rows R;
-        rows_for(R, s);
-        if (s < t.nk) issue(L, t, s, s, R);
-      }
+      for (int s = 0; s < kStages - 1; ++s)
+        if (s < t.nk) issue(L, s, s);
     };
     Loads cur;
     setup(cur, tc);
@@ -244,10 +190,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
         if (kt + kStages - 1 < nk) {
           int ps = stage - 1;
           if (ps < 0) ps += kStages;
-          fetch_ids(tc, kt + kStages);                     // row numbers for the request of the next iteration
-          Rows R;
-          rows_for(R, kt + kStages - 1);
-          issue(cur, tc, kt + kStages - 1, ps, R);         // the buffer of k tile kt-1: every compute wave is past it
+          issue(cur, kt + kStages - 1, ps);                // the buffer of k tile kt-1: every compute wave is past it
         }
         if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }
         if (kt == nk - 1 && more) setup(nxt, tn);
@@ -270,23 +213,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
   int offA[2], keyA[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) { const int r = wm + i * 32 + fr; offA[i] = r * kTK; keyA[i] = (r >> 1) & 7; }
-  int offB[4], keyB[4];  // KC only
-  uint32_t tr_lo[4], tr_hi[4];  // NC only: LDS byte offsets (inside a stage's B region) of this lane's transposing reads
-  if constexpr (!P::kBNC) {
+  int offB[4], keyB[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { const int r = wn + j * 32 + fr; offB[j] = kTM * kTK + r * kTK; keyB[j] = (r >> 1) & 7; }
-  } else {
-    // lane s of a 16-lane group points at row (k base + s/4), columns 4*(s%4)..+3 of a 4 x 16 block and
-    // receives column s of that block, four consecutive k.  Low half: k = 8*(lane/32) + 0..3, high half +4.
-    const int gq = lane >> 4, s = lane & 15;
-    const int k_lo = 8 * (gq >> 1) + (s >> 2), k_hi = k_lo + 4;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = wn + j * 32 + 16 * (gq & 1) + 4 * (s & 3);
-      tr_lo[j] = (uint32_t)(k_lo * 256 + (((n >> 3) ^ (2 * (k_lo & 7))) << 3) + (n & 7)) * 2u;
-      tr_hi[j] = (uint32_t)(k_hi * 256 + (((n >> 3) ^ (2 * (k_hi & 7))) << 3) + (n & 7)) * 2u;
-    }
-  }
+  for (int j = 0; j < 4; ++j) { const int r = wn + j * 32 + fr; offB[j] = kTM * kTK + r * kTK; keyB[j] = (r >> 1) & 7; }
 
   for (;;) {
     f32x16 acc[2][4];
@@ -311,26 +240,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
         const int c = ks * 2 + fc;
 #pragma unroll
         for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
-        if constexpr (!P::kBNC) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
-        } else {
-          // k16 step ks starts 16 rows = 8192 bytes further; that does not change (k & 7), so the swizzle holds
-          const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
-          uint32_t alo[4], ahi[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
-          u32x2 o[8];
-          if (ks == 0) tr_read8<0>(o, alo, ahi);
-          else if (ks == 1) tr_read8<8192>(o, alo, ahi);
-          else if (ks == 2) tr_read8<16384>(o, alo, ahi);
-          else tr_read8<24576>(o, alo, ahi);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
-            fb[j] = __builtin_bit_cast(bf16x8, w);
-          }
-        }
+        for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll

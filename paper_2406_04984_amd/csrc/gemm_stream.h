@@ -13,10 +13,21 @@
 //    wave thus writes 64 contiguous bytes of each of two rows per instruction.  While the compute waves store, the
 //    loaders are already two k tiles into the next tile.
 //
-// There is exactly one workgroup barrier per k tile of the stream, executed by all six waves.
+// There is exactly one workgroup barrier per k tile of the stream, executed by all six waves.  (An extra barrier at
+// the end of every tile, releasing its last stage before the stores so that the loaders request a third k tile
+// during the epilogue, was measured and did not pay.)
 //
-// A policy P of this kernel provides, besides locate / a_row / b_row_ids or b_row_id_src / b_row_ptr (see
-// gemm_mfma.h):
+// A policy P of this kernel provides locate and a_row (see gemm_mfma.h) and
+//   static constexpr bool kRowIdsInMemory;
+//       false: __device__ int b_row_ids(const TileCoord&, int k) const;  number of the B row that holds k (plain
+//              arithmetic, no memory access), any valid row for k beyond the contraction length;
+//       true:  __device__ const int32_t* b_row_id_src(const TileCoord&, int k0) const;  where the numbers of the B rows
+//              of k0 .. k0 + 63 are stored (valid rows also beyond the contraction length: those products are zero);
+//              called for k0 = 0, 64, ... below 64 * nk.  The numbers travel like the operands: a 4-byte-per-lane
+//              global -> LDS load puts the 64 numbers of a k tile into a small ring in LDS one position ahead of
+//              the operand request that uses them;
+//   __device__ const uint16_t* b_row_ptr(int row) const;          start of B row `row`; rows are TileCoord::Ncols
+//                                                                 elements apart
 //   __device__ uint16_t* out_base(const TileCoord&) const;        row 0, column 0 of the group's output; the leading
 //                                                                 dimension is TileCoord::Ncols (a multiple of 32)
 //   __device__ bool out_row_ok(const TileCoord&, int m) const;    is row m of the group's output stored?  (false for
@@ -80,45 +91,67 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_stream_kernel(P p, int n
         if (++k_d == t_d.nk) { wg_d += step; k_d = 0; ok_d = next_tile(wg_d, t_d); }
       }
     };
+    // B: a wave-load covers two k rows (lanes 0..31 the even one, lanes 32..63 the odd one), 512 bytes of each.
+    // Lane l fetches the 16-byte chunk (l & 31) ^ (2 * (row & 7)) of its row (the LDS swizzle); row & 7 only
+    // depends on i & 3, so four column offsets per tile cover all the loads.
+    const int half = lane >> 5;
+    const uint16_t* bcol[4];
+    auto setup_b = [&]() {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
+        int col = t_o.n0 + chunk * 8;
+        col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;              // clamp (columns beyond Ncols are never stored)
+        bcol[q] = p.b_row_ptr(0) + col;
+      }
+    };
     auto request_operands = [&]() {
       if (!ok_o) return;
-      int ids = 0;   // lane l: number of the B row of k = 64 * k_o + l
+      // ids[i]: number of the B row this lane fetches in its i-th load, k = 64 * k_o + 2 * (lw * LB + i) + half
+      int ids[LB];
       if constexpr (P::kRowIdsInMemory) {
-        const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(idring + (n_o & (kIdRingSlots - 1)) * 64 + lane);
-        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(ids) : "v"(a) : "memory");
+        // out of the ring; one asm block with its own wait (through plain loads the compiler would first drain every
+        // outstanding operand load)
+        const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(
+            idring + (n_o & (kIdRingSlots - 1)) * 64 + 2 * lw * LB + half);
+        static_assert(LB == 16, "the block below reads sixteen row numbers");
+        asm volatile(
+            "ds_read_b32 %0, %16\n\tds_read_b32 %1, %16 offset:8\n\tds_read_b32 %2, %16 offset:16\n\t"
+            "ds_read_b32 %3, %16 offset:24\n\tds_read_b32 %4, %16 offset:32\n\tds_read_b32 %5, %16 offset:40\n\t"
+            "ds_read_b32 %6, %16 offset:48\n\tds_read_b32 %7, %16 offset:56\n\tds_read_b32 %8, %16 offset:64\n\t"
+            "ds_read_b32 %9, %16 offset:72\n\tds_read_b32 %10, %16 offset:80\n\tds_read_b32 %11, %16 offset:88\n\t"
+            "ds_read_b32 %12, %16 offset:96\n\tds_read_b32 %13, %16 offset:104\n\tds_read_b32 %14, %16 offset:112\n\t"
+            "ds_read_b32 %15, %16 offset:120\n\ts_waitcnt lgkmcnt(0)"
+            : "=&v"(ids[0]), "=&v"(ids[1]), "=&v"(ids[2]), "=&v"(ids[3]), "=&v"(ids[4]), "=&v"(ids[5]), "=&v"(ids[6]),
+              "=&v"(ids[7]), "=&v"(ids[8]), "=&v"(ids[9]), "=&v"(ids[10]), "=&v"(ids[11]), "=&v"(ids[12]),
+              "=&v"(ids[13]), "=&v"(ids[14]), "=&v"(ids[15])
+            : "v"(a)
+            : "memory");
+      } else {
+#pragma unroll
+        for (int i = 0; i < LB; ++i) ids[i] = p.b_row_ids(t_o, k_o * kTK + 2 * (lw * LB + i) + half);
       }
       uint16_t* sa = smem + stage_o * kStageElems;
       uint16_t* sb = sa + kTM * kTK;
 #pragma unroll
       for (int i = 0; i < LA; ++i)
         __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + k_o * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
+      const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
 #pragma unroll
       for (int i = 0; i < LB; ++i) {
-        int r0, r1;   // wave-uniform numbers of the two B rows of this load
-        if constexpr (P::kRowIdsInMemory) {
-          r0 = __builtin_amdgcn_readlane(ids, 2 * (lw * LB + i));
-          r1 = __builtin_amdgcn_readlane(ids, 2 * (lw * LB + i) + 1);
-        } else {
-          const int k0 = k_o * kTK + 2 * (lw * LB + i);
-          r0 = p.b_row_ids(t_o, k0);
-          r1 = p.b_row_ids(t_o, k0 + 1);
-        }
-        const int krow = 2 * (lw * LB + i) + (lane >> 5);             // this lane's k row inside the tile
-        const int chunk = (lane & 31) ^ (2 * (krow & 7));             // logical 16-byte chunk this lane fetches
-        int col = t_o.n0 + chunk * 8;
-        col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;              // clamp (columns beyond Ncols are never stored)
-        const uint16_t* src = p.b_row_ptr((lane >> 5) ? r1 : r0) + col;
+        const char* src = reinterpret_cast<const char*>(bcol[i & 3]) + (uint64_t)(uint32_t)ids[i] * row_bytes;
         __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (lw * LB + i) * 512), 16, 0, 0);
       }
       ++n_o;
       stage_o = stage_o + 1 == kStages ? 0 : stage_o + 1;
       if (++k_o == t_o.nk) {
         wg_o += step; k_o = 0; ok_o = next_tile(wg_o, t_o);
-        if (ok_o) setup();
+        if (ok_o) { setup(); setup_b(); }
       }
     };
 
     setup();
+    setup_b();
     if constexpr (P::kRowIdsInMemory) {
 #pragma unroll
       for (int s = 0; s < kStages; ++s) request_ids();
