@@ -32,6 +32,7 @@ constexpr int kSlotPad = 192;
 // scores to p + s*T*n_blocks and the top-e kernel adds the partials in a fixed order.
 struct ProbRouter {
   static constexpr bool kBNC = false;
+  static constexpr bool kAMC = false;
   static constexpr bool kRowIdsInMemory = false;
   static constexpr int kStoreBarriers = 0;
   const uint16_t* h; const uint16_t* Wg; float* p;
@@ -62,24 +63,25 @@ struct ProbRouter {
 // Token-major, B contiguous along k: rows = tokens of the group (gathered through perm), columns =
 // the block's neurons.  What is written depends on MODE:
 //   kTokScores: key scores, fp32, by entry.
-//   kTokMasked: the activation gradient, masked by A' > 0, bf16, both slot-major (DS') and neuron-major (DS'^T).
+//   kTokMasked: the activation gradient, masked by A' > 0, bf16, slot-major (DS').
 //   kTokRelu:   ReLU of the scores (Eq. 2 without a selection: the batch-union evaluation of Algorithm 1), bf16,
-//               written through the same two pointers, slot-major and neuron-major.
+//               written through the same pointer.
 constexpr int kTokScores = 0, kTokMasked = 1, kTokRelu = 2;
 
 template <int MODE>
 struct ProbTokKC {
   static constexpr bool kBNC = false;
   static constexpr bool kRowIdsInMemory = false;
-  static constexpr int kStoreBarriers = MODE == kTokScores ? 0 : 1;
+  static constexpr bool kAMC = false;
+  static constexpr int kStoreBarriers = 0;
   const uint16_t* X;          // h (scores) or dOut (activation gradient), [T, d]
   const uint16_t* W;          // K or V, [N, d]
-  const int32_t* perm; const int32_t* group_off; const int32_t* goffp;
+  const int32_t* perm; const int32_t* group_off;
   TokenSched sched;
   int e, bs, bsp, d;
   float* sc;                  // kTokScores: [T*e, bs]
   const uint16_t* Ap;         // kTokMasked: A' [slots, bsp]
-  uint16_t* DS; uint16_t* DST;
+  uint16_t* DS;               // kTokMasked / kTokRelu: [slots, bsp]
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
     if (!locate_token_tile(sched, group_off, wg, (bs + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
@@ -116,7 +118,7 @@ struct ProbTokKC {
         }
       }
     } else {
-      // step 1, slot-major: 8 columns per thread; mask by A' > 0, store DS', keep the masked value in LDS
+      // slot-major: 8 columns per thread; mask by A' > 0 (or by sign), store DS'
       const int c = (tid & 31) * 8, n = tc.n0 + c;
 #pragma unroll
       for (int it = 0; it < kEpiRows / 8; ++it) {
@@ -145,23 +147,6 @@ struct ProbTokKC {
           for (int z = 0; z < 8; ++z) x[z] = (row_in && n + z < bs && x[z] > 0.f) ? x[z] : 0.f;
         }
         if (row_in && n < bsp) Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(DS) + (size_t)(tc.slot0 + m) * bsp + n, x);
-        f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
-        *reinterpret_cast<f32x4*>(&rows[tile_index(r, c)]) = a;
-        *reinterpret_cast<f32x4*>(&rows[tile_index(r, c + 4)]) = b;
-      }
-      MEFT_BARRIER_LDS();
-      // step 2, neuron-major: column n, 8 consecutive slots -> one 16-byte store into DS'^T
-      const int Mgp = round_up64(tc.Mrows);
-      uint16_t* base = DST + (size_t)as_const(goffp)[tc.g] * bs;
-#pragma unroll
-      for (int it = 0; it < kEpiRows / 8; ++it) {
-        const int cc = tid, r8 = it * 8;   // kTN == 256 == threads
-        const int nn = tc.n0 + cc, m = tc.m0 + r0 + r8;
-        if (nn >= bs || m >= Mgp) continue;
-        float x[8];
-#pragma unroll
-        for (int z = 0; z < 8; ++z) x[z] = rows[tile_index(r8 + z, cc)];
-        Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(base) + (size_t)nn * Mgp + m, x);
       }
     }
   }
@@ -171,6 +156,7 @@ struct ProbTokKC {
 // W = K: dh).  A is slot-major [slots, bsp] with zero padding in columns bs..bsp.
 struct ProbTokNC {
   static constexpr bool kBNC = true;
+  static constexpr bool kAMC = false;
   static constexpr bool kRowIdsInMemory = false;
   const uint16_t* A;          // A' or DS'
   const uint16_t* W;          // V or K, [N, d]
@@ -193,17 +179,22 @@ struct ProbTokNC {
   __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < tc.Mrows; }
 };
 
-// Neuron-major, B contiguous along n: G_b[bs, d] = AT_b[bs, slots] . X[token(slot), :]
-// (AT = A'^T, X = dOut: dV;  AT = DS'^T, X = h: dK).  Only rows whose neuron is touched are written.
-struct ProbNeuNC {
+// Neuron-major, both operands indexed by the contraction index (slot) in their rows:
+//   G_b[bs, d] = sum over the slots of group b of A[slot, 0:bs]^T . X[token(slot), :]
+// (A = A', X = dOut: dV;  A = DS', X = h: dK).  A is the slot-major matrix the token-major kernels write and read,
+// so no transposed copy of the activations exists.  The contraction length is padded to 64: the padding rows of A
+// come from a row of zeros, those of X are any valid rows.  Only rows whose neuron is touched are written.
+struct ProbNeuTN {
   static constexpr bool kBNC = true;
+  static constexpr bool kAMC = true;
   static constexpr bool kRowIdsInMemory = true;
-  const uint16_t* AT;         // per group [bs, Mgp] at element offset goffp[g]*bs
+  const uint16_t* A;          // [slots, bsp]
+  const uint16_t* zrow;       // bsp zeros
   const uint16_t* X;          // [T, d]
-  const int32_t* group_off; const int32_t* goffp; const int32_t* tok_of_slot;
+  const int32_t* group_off; const int32_t* tok_of_slot;
   const int32_t* flag;        // [N] > 0 where some token selected the neuron
   TokenSched sched;           // only the group lists are used: every group has the same number of tiles
-  int bs, d;
+  int bs, bsp, d;
   uint16_t* G;                // dV or dK [N, d]
   __device__ bool locate(int wg, TileCoord& tc) const {
     const int tm = (bs + kTM - 1) / kTM, tn = (d + kTN - 1) / kTN;
@@ -218,10 +209,11 @@ struct ProbNeuNC {
     tc.aux = rows;
     return true;
   }
-  __device__ const uint16_t* a_row(const TileCoord& tc, int m) const {
-    return AT + (size_t)as_const(goffp)[tc.g] * bs + (size_t)(m < bs ? m : bs - 1) * round_up64(tc.aux);
+  __device__ int a_cols(const TileCoord&) const { return bsp; }
+  __device__ const uint16_t* a_krow(const TileCoord& tc, int k) const {
+    return k < tc.aux ? A + (size_t)(tc.slot0 + k) * bsp : zrow;
   }
-  // tok_of_slot is padded by kSlotPad valid entries, which covers k0 + 63 up to the padded contraction length + 127
+  // tok_of_slot is padded by kSlotPad valid entries, which covers the padded contraction length
   __device__ const int32_t* b_row_id_src(const TileCoord& tc, int k0) const { return tok_of_slot + tc.slot0 + k0; }
   __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }
   __device__ uint16_t* out_base(const TileCoord& tc) const { return G + (size_t)tc.g * bs * d; }
@@ -263,12 +255,11 @@ __global__ __launch_bounds__(64) void blocks_from_idx_kernel(const int32_t* __re
   for (int q = base + lane; q < e; q += 64) sblk[(size_t)t * e + q] = -1;
 }
 
-// After fill_groups: slot -> token, entry -> slot, and the prefix of 64-padded group sizes.
+// After fill_groups: slot -> token (padded by kSlotPad valid entries) and entry -> slot.
 __global__ __launch_bounds__(256) void slot_maps_kernel(const int32_t* __restrict__ perm,
                                                         const int32_t* __restrict__ group_off, int n_groups, int e,
                                                         int32_t* __restrict__ tok_of_slot,
-                                                        int32_t* __restrict__ slot_of_ent,
-                                                        int32_t* __restrict__ goffp) {
+                                                        int32_t* __restrict__ slot_of_ent) {
   const int n_slots = group_off[n_groups];
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < n_slots) {
@@ -278,26 +269,14 @@ __global__ __launch_bounds__(256) void slot_maps_kernel(const int32_t* __restric
   } else if (i < n_slots + kSlotPad) {
     tok_of_slot[i] = 0;
   }
-  if (blockIdx.x == 0) {
-    // serial prefix over groups by one thread per 256-group chunk would need a scan; n_groups is small
-    if (threadIdx.x == 0) {
-      int acc = 0;
-      for (int g = 0; g < n_groups; ++g) {
-        goffp[g] = acc;
-        acc += round_up64(group_off[g + 1] - group_off[g]);
-      }
-      goffp[n_groups] = acc;
-    }
-  }
 }
 
-// Backward: scatter the saved activations into A' (slot-major) and A'^T (neuron-major), and mark
-// touched neurons.  Both buffers must be zero before.  One thread per (token, neuron) pair.
+// Backward: scatter the saved activations into A' (slot-major) and mark touched neurons.  A' and the flags must
+// be zero before.  One thread per (token, neuron) pair.
 __global__ void scatter_act_kernel(const int32_t* __restrict__ idx, const float* __restrict__ act, int P, int k,
                                    int N, int bs, int bsp, int e, const int32_t* __restrict__ sblk,
-                                   const int32_t* __restrict__ slot_of_ent, const int32_t* __restrict__ group_off,
-                                   const int32_t* __restrict__ goffp, uint16_t* __restrict__ Ap,
-                                   uint16_t* __restrict__ ApT, int32_t* __restrict__ flag) {
+                                   const int32_t* __restrict__ slot_of_ent, uint16_t* __restrict__ Ap,
+                                   int32_t* __restrict__ flag) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= P) return;
   const int t = p / k;
@@ -311,8 +290,6 @@ __global__ void scatter_act_kernel(const int32_t* __restrict__ idx, const float*
   const int slot = slot_of_ent[t * e + q];
   const uint16_t v = (uint16_t)f32_to_bf16_bits(act[p]);
   Ap[(size_t)slot * bsp + r] = v;
-  const int s0 = group_off[b], Mgp = round_up64(group_off[b + 1] - s0);
-  ApT[(size_t)goffp[b] * bs + (size_t)r * Mgp + (slot - s0)] = v;
 }
 
 // out[t, :] = sum over the token's entries of part[slot(entry), :] (bf16 partials, fp32 sum), rounded to bf16.

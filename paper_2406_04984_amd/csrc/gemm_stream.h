@@ -39,6 +39,33 @@
 
 namespace meft {
 
+// Twelve transposing LDS reads of one k16 step (the two m-contiguous A fragments and the four n-contiguous B
+// fragments, low and high k half each) followed by the wait for them; one asm block for the reason given at
+// tr_read8.  xa = {A0 low, A0 high, A1 low, A1 high}.
+template <int OFFA, int OFFB>
+__device__ __forceinline__ void tr_read12(u32x2 (&oa)[4], u32x2 (&ob)[8], const uint32_t (&xa)[4],
+                                          const uint32_t (&blo)[4], const uint32_t (&bhi)[4]) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %12 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %1, %13 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %2, %14 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %3, %15 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %4, %16 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %5, %17 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %6, %18 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %7, %19 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %8, %20 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %9, %21 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %10, %22 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %11, %23 offset:%25\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(oa[0]), "=&v"(oa[1]), "=&v"(oa[2]), "=&v"(oa[3]), "=&v"(ob[0]), "=&v"(ob[1]), "=&v"(ob[2]),
+        "=&v"(ob[3]), "=&v"(ob[4]), "=&v"(ob[5]), "=&v"(ob[6]), "=&v"(ob[7])
+      : "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "v"(blo[0]), "v"(bhi[0]), "v"(blo[1]), "v"(bhi[1]),
+        "v"(blo[2]), "v"(bhi[2]), "v"(blo[3]), "v"(bhi[3]), "n"(OFFA), "n"(OFFB)
+      : "memory");
+}
+
 template <class P>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_stream_kernel(P p, int n_tiles_bound) {
   static_assert(P::kBNC, "the streaming kernel covers the n-contiguous B layouts");
@@ -69,12 +96,23 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_stream_kernel(P p, int n
     int wg_o = blockIdx.x, k_o = 0, n_o = 0, stage_o = 0;
     bool ok_o = true;
     TileCoord t_o = tc;
+    // A, k-contiguous: a wave-load covers 8 rows (m) x 128 bytes; fixed row pointers per tile, advanced by k.
+    // A, m-contiguous (P::kAMC): a wave-load covers 4 rows (k) x 256 bytes; lane l fetches the 16-byte chunk
+    // (l & 15) ^ (4 * (row & 3)) of its row (the LDS swizzle; row & 3 == (l >> 4) & 3 for every load), so one column
+    // offset per tile serves all the loads.
     const uint16_t* pa[LA];
+    int acol = 0;
     auto setup = [&]() {
+      if constexpr (P::kAMC) {
+        const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
+        const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
+        acol = col > last ? last : col;                                 // clamp (rows beyond Mrows are never stored)
+      } else {
 #pragma unroll
-      for (int i = 0; i < LA; ++i) {
-        const int row = (lw * LA + i) * 8 + lr8;
-        pa[i] = p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        for (int i = 0; i < LA; ++i) {
+          const int row = (lw * LA + i) * 8 + lr8;
+          pa[i] = p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        }
       }
     };
     //   row numbers (only where they sit in memory)
@@ -134,8 +172,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_stream_kernel(P p, int n
       uint16_t* sa = smem + stage_o * kStageElems;
       uint16_t* sb = sa + kTM * kTK;
 #pragma unroll
-      for (int i = 0; i < LA; ++i)
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + k_o * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
+      for (int i = 0; i < LA; ++i) {
+        if constexpr (P::kAMC) {
+          const uint16_t* src = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4)) + acol;
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sa + (lw * LA + i) * 4 * kTM), 16, 0, 0);
+        } else {
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + k_o * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
+        }
+      }
       const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
 #pragma unroll
       for (int i = 0; i < LB; ++i) {
@@ -183,9 +227,21 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_stream_kernel(P p, int n
   // -------------------------------------------------------------------- compute waves
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
   const int fr = lane & 31, fc = lane >> 5;
-  int offA[2], keyA[2];
+  int offA[2], keyA[2];            // k-contiguous A
+  uint32_t tra_lo[2], tra_hi[2];   // m-contiguous A: LDS byte offsets (inside a stage) of the transposing reads
 #pragma unroll
   for (int i = 0; i < 2; ++i) { const int r = wm + i * 32 + fr; offA[i] = r * kTK; keyA[i] = (r >> 1) & 7; }
+  {
+    // rows of 128 m = 16 chunks of 16 B; logical chunk c of row k sits at chunk c ^ (4 * (k & 3))
+    const int gq = lane >> 4, s = lane & 15;
+    const int k_lo = 8 * (gq >> 1) + (s >> 2), k_hi = k_lo + 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int m = wm + i * 32 + 16 * (gq & 1) + 4 * (s & 3);
+      tra_lo[i] = (uint32_t)(k_lo * kTM + (((m >> 3) ^ (4 * (k_lo & 3))) << 3) + (m & 7)) * 2u;
+      tra_hi[i] = (uint32_t)(k_hi * kTM + (((m >> 3) ^ (4 * (k_hi & 3))) << 3) + (m & 7)) * 2u;
+    }
+  }
   uint32_t tr_lo[4], tr_hi[4];  // LDS byte offsets (inside a stage's B region) of this lane's transposing reads
   {
     // lane s of a 16-lane group points at row (k base + s/4), columns 4*(s%4)..+3 of a 4 x 16 block and
@@ -219,19 +275,35 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_stream_kernel(P p, int n
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         bf16x8 fa[2], fb[4];
-        const int c = ks * 2 + fc;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
-        // k16 step ks starts 16 rows = 8192 bytes further; that does not change (k & 7), so the swizzle holds
+        // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 bytes); that changes neither
+        // (k & 7) nor (k & 3), so the swizzles hold
         const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
         uint32_t alo[4], ahi[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
         u32x2 o[8];
-        if (ks == 0) tr_read8<0>(o, alo, ahi);
-        else if (ks == 1) tr_read8<8192>(o, alo, ahi);
-        else if (ks == 2) tr_read8<16384>(o, alo, ahi);
-        else tr_read8<24576>(o, alo, ahi);
+        if constexpr (P::kAMC) {
+          const uint32_t abase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st);
+          const uint32_t xa[4] = {abase + tra_lo[0], abase + tra_hi[0], abase + tra_lo[1], abase + tra_hi[1]};
+          u32x2 oa[4];
+          if (ks == 0) tr_read12<0, 0>(oa, o, xa, alo, ahi);
+          else if (ks == 1) tr_read12<4096, 8192>(oa, o, xa, alo, ahi);
+          else if (ks == 2) tr_read12<8192, 16384>(oa, o, xa, alo, ahi);
+          else tr_read12<12288, 24576>(oa, o, xa, alo, ahi);
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            const u32x4 w = {oa[2 * i].x, oa[2 * i].y, oa[2 * i + 1].x, oa[2 * i + 1].y};
+            fa[i] = __builtin_bit_cast(bf16x8, w);
+          }
+        } else {
+          const int c = ks * 2 + fc;
+#pragma unroll
+          for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
+          if (ks == 0) tr_read8<0>(o, alo, ahi);
+          else if (ks == 1) tr_read8<8192>(o, alo, ahi);
+          else if (ks == 2) tr_read8<16384>(o, alo, ahi);
+          else tr_read8<24576>(o, alo, ahi);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};

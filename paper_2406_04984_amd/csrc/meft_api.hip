@@ -128,7 +128,7 @@ struct RouteWs {
 // index structures of the (token, block) dispatch, common to forward and backward
 struct DispatchWs {
   int32_t *sblk = nullptr, *cnt = nullptr, *group_off = nullptr, *tile_off = nullptr, *perm = nullptr,
-          *tok_of_slot = nullptr, *slot_of_ent = nullptr, *goffp = nullptr, *sched_len = nullptr;
+          *tok_of_slot = nullptr, *slot_of_ent = nullptr, *sched_len = nullptr;
   int2* sched_pairs = nullptr;
   void carve(const meft_shape& s, Carver& c) {
     const size_t n_ent = (size_t)s.T * s.top_e;
@@ -139,7 +139,6 @@ struct DispatchWs {
     perm = c.take<int32_t>(n_ent);
     tok_of_slot = c.take<int32_t>(n_ent + kSlotPad);   // padded: see kSlotPad
     slot_of_ent = c.take<int32_t>(n_ent);
-    goffp = c.take<int32_t>((size_t)s.n_blocks + 1);
     sched_len = c.take<int32_t>(kXcd);
     sched_pairs = c.take<int2>((size_t)kXcd * sched_cap(s));
   }
@@ -170,23 +169,21 @@ struct BwdWs : DispatchWs {
   int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted;
   // dense path
   int32_t *flag, *chunk_cnt;
-  uint16_t *Ap, *ApT, *DS, *DST, *part;
+  uint16_t *zrow, *Ap, *DS, *part;
   size_t bytes;
   BwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
     const size_t P = (size_t)s.T * s.top_k;
     ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = flag = chunk_cnt = nullptr;
-    Ap = ApT = DS = DST = nullptr; part = nullptr;
+    zrow = Ap = DS = nullptr; part = nullptr;
     if (use_dense(s)) {
       carve(s, c);
       const size_t n_ent = (size_t)s.T * s.top_e;
-      const size_t slots_p = n_ent + (size_t)64 * s.n_blocks;   // group sizes padded to 64
       chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
-      flag = c.take<int32_t>(s.N);
-      Ap = c.take<uint16_t>(n_ent * round64(s.block_size));      // Ap and ApT adjacent: cleared by one fill
-      ApT = c.take<uint16_t>(slots_p * s.block_size);
+      flag = c.take<int32_t>(s.N);                               // flag, zrow and Ap adjacent: cleared by one fill
+      zrow = c.take<uint16_t>(round64(s.block_size));
+      Ap = c.take<uint16_t>(n_ent * round64(s.block_size));
       DS = c.take<uint16_t>(n_ent * round64(s.block_size));
-      DST = c.take<uint16_t>(slots_p * s.block_size);
       part = c.take<uint16_t>(n_ent * s.d);
     } else {
       ds = c.take<float>(P);
@@ -321,13 +318,12 @@ bool union_geom(const meft_shape& s, UnionGeom& g) {
 
 struct UnionWs : DispatchWs {
   int32_t *flag, *chunk_cnt, *rowflag;
-  uint16_t *Kc, *Vc, *dKc, *dVc, *Ap, *ApT, *DS, *DST, *part;
+  uint16_t *Kc, *Vc, *dKc, *dVc, *zrow, *Ap, *DS, *part;
   size_t bytes;
   UnionWs(const meft_shape& s, const UnionGeom& g, void* ws) {
     Carver c(ws);
     carve(g.vs, c);
     const size_t n_ent = (size_t)s.T * g.nvb, rows = (size_t)g.nvb * g.vbs;
-    const size_t slots_p = (size_t)g.nvb * round64(s.T);
     chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
     flag = c.take<int32_t>(s.N);
     rowflag = c.take<int32_t>(rows);
@@ -335,10 +331,9 @@ struct UnionWs : DispatchWs {
     Vc = c.take<uint16_t>(rows * s.d);
     dKc = c.take<uint16_t>(rows * s.d);
     dVc = c.take<uint16_t>(rows * s.d);
+    zrow = c.take<uint16_t>(g.vbs);
     Ap = c.take<uint16_t>(n_ent * g.vbs);
-    ApT = c.take<uint16_t>(slots_p * g.vbs);
     DS = c.take<uint16_t>(n_ent * g.vbs);
-    DST = c.take<uint16_t>(slots_p * g.vbs);
     part = c.take<uint16_t>(n_ent * s.d);
     bytes = c.off < 256 ? 256 : c.off;
   }
@@ -454,7 +449,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
               s.n_blocks, BM, w.group_off, w.tile_off, w.perm);
   if (dense) {
     MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + kSlotPad + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
-                s.n_blocks, s.top_e, w.tok_of_slot, w.slot_of_ent, w.goffp);
+                s.n_blocks, s.top_e, w.tok_of_slot, w.slot_of_ent);
     MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks,
                 sched_cap(s), w.sched_pairs, w.sched_len);
   }
@@ -494,7 +489,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
   if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
   if (dense) {
     ProbTokKC<kTokScores> ps{};
-    ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.goffp = w.goffp; ps.sched = sched;
+    ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.sched = sched;
     ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
     launch_gemm_mfma("score_gemm", ps, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
   } else {
@@ -559,12 +554,12 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
                 st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
     launch_dispatch(s, w, kGemmBM, true, st);
-    // flag, A', A'^T start from zero (flag..ApT are adjacent in the workspace); 4-byte fill
+    // flag, the row of zeros and A' start from zero (adjacent in the workspace); 4-byte fill
     const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.DS) - reinterpret_cast<char*>(w.flag)) / 4;
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
                 clear_words, 0);
     MEFT_LAUNCH("scatter_act", scatter_act_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, act, P, s.top_k,
-                s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.group_off, w.goffp, w.Ap, w.ApT, w.flag);
+                s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.Ap, w.flag);
     const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
     MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
     MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
@@ -573,17 +568,17 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     // every listed group has the same tiles; in the worst case one XCD holds all groups
     const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
     const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
-    ProbNeuNC pn{};
-    pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
-    pn.sched = sched; pn.bs = s.block_size; pn.d = s.d;
+    ProbNeuTN pn{};
+    pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag; pn.zrow = w.zrow;
+    pn.sched = sched; pn.bs = s.block_size; pn.bsp = bsp; pn.d = s.d;
     // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
     // gathers the same dOut rows as the activation-gradient GEMM that follows it
-    pn.AT = w.ApT; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
+    pn.A = w.Ap; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
     launch_gemm_stream("dV_gemm", pn, neu_grid, st);
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<kTokMasked> pg{};
-    pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
-    pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
+    pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
+    pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS;
     launch_gemm_mfma("dact_gemm", pg, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
     if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     if (dh) {
@@ -593,7 +588,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
       launch_gemm_stream("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
-    pn.AT = w.DST; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
+    pn.A = w.DS; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
     launch_gemm_stream("dK_gemm", pn, neu_grid, st);
     return launch_status();
   }
@@ -620,15 +615,18 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
 }
 
 // Shared front part of the batch-union forward and backward: index structure from n_S, tile schedule, compacted
-// K and V, and A' = ReLU(h K[S]^T) in both layouts.
+// K and V, and A' = ReLU(h K[S]^T).
 static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& w, const void* h, const void* K,
                         const void* V, const int32_t* S, const int32_t* n_S, hipStream_t st) {
   const size_t n_slots = (size_t)g.nvb * s.T, n_rows = (size_t)g.nvb * g.vbs;
   const size_t n_thr = (n_slots + kSlotPad) > n_rows ? (n_slots + kSlotPad) : n_rows;
   MEFT_LAUNCH("union_maps", union_maps_kernel, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, n_S, g.cap,
-              s.T, g.vbs, g.nvb, w.sblk, w.perm, w.tok_of_slot, w.slot_of_ent, w.group_off, w.goffp, w.rowflag);
+              s.T, g.vbs, g.nvb, w.sblk, w.perm, w.tok_of_slot, w.slot_of_ent, w.group_off, w.rowflag);
   MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, g.nvb, sched_cap(g.vs),
               w.sched_pairs, w.sched_len);
+  // the row of zeros that pads the contraction over tokens in the weight-gradient GEMMs (vbs % 64 == 0)
+  MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((g.vbs / 2 + 255) / 256), dim3(256), 0, st,
+              reinterpret_cast<int32_t*>(w.zrow), (size_t)g.vbs / 2, 0);
   const int rows_grid = (int)(n_rows < 4096 ? n_rows : 4096);
   MEFT_LAUNCH("gather_rows", gather_rows_kernel, dim3(rows_grid), dim3(256), 0, st, static_cast<const uint16_t*>(K),
               S, n_S, g.cap, s.N, s.d, g.vbs, w.Kc);
@@ -637,8 +635,8 @@ static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& 
   const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(g.vs), sched_max_tiles(g.vs)};
   ProbTokKC<kTokRelu> pr{};
   pr.X = static_cast<const uint16_t*>(h); pr.W = w.Kc; pr.perm = w.perm; pr.group_off = w.group_off;
-  pr.goffp = w.goffp; pr.sched = sched; pr.e = g.nvb; pr.bs = g.vbs; pr.bsp = g.vbs; pr.d = s.d;
-  pr.DS = w.Ap; pr.DST = w.ApT;
+  pr.sched = sched; pr.e = g.nvb; pr.bs = g.vbs; pr.bsp = g.vbs; pr.d = s.d;
+  pr.DS = w.Ap;
   launch_gemm_mfma("union_score_gemm", pr, tile_bound(g.vs, (g.vbs + kTN - 1) / kTN), st);
 }
 
@@ -707,8 +705,8 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(g.vs), sched_max_tiles(g.vs)};
   const uint16_t *hh = static_cast<const uint16_t*>(h), *gg = static_cast<const uint16_t*>(dOut);
   ProbTokKC<kTokMasked> pg{};
-  pg.X = gg; pg.W = w.Vc; pg.perm = w.perm; pg.group_off = w.group_off; pg.goffp = w.goffp; pg.sched = sched;
-  pg.e = g.nvb; pg.bs = g.vbs; pg.bsp = g.vbs; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS; pg.DST = w.DST;
+  pg.X = gg; pg.W = w.Vc; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
+  pg.e = g.nvb; pg.bs = g.vbs; pg.bsp = g.vbs; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS;
   launch_gemm_mfma("union_dact_gemm", pg, tile_bound(g.vs, (g.vbs + kTN - 1) / kTN), st);
   if (dh) {
     ProbTokNC ph{};
@@ -719,12 +717,12 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   }
   const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
   const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
-  ProbNeuNC pn{};
-  pn.group_off = w.group_off; pn.goffp = w.goffp; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;
-  pn.sched = sched; pn.bs = g.vbs; pn.d = s.d;
-  pn.AT = w.ApT; pn.X = gg; pn.G = w.dVc;
+  ProbNeuTN pn{};
+  pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag; pn.zrow = w.zrow;
+  pn.sched = sched; pn.bs = g.vbs; pn.bsp = g.vbs; pn.d = s.d;
+  pn.A = w.Ap; pn.X = gg; pn.G = w.dVc;
   launch_gemm_stream("union_dV_gemm", pn, neu_grid, st);
-  pn.AT = w.DST; pn.X = hh; pn.G = w.dKc;
+  pn.A = w.DS; pn.X = hh; pn.G = w.dKc;
   launch_gemm_stream("union_dK_gemm", pn, neu_grid, st);
   const int rows_grid = g.cap < 4096 ? g.cap : 4096;
   MEFT_LAUNCH("scatter_rows", scatter_rows_kernel, dim3(rows_grid), dim3(256), 0, st, w.dVc, S, n_S, s.N, s.d, g.cap,

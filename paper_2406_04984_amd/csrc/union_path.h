@@ -29,7 +29,6 @@ __global__ __launch_bounds__(256) void union_maps_kernel(const int32_t* __restri
                                                          int32_t* __restrict__ tok_of_slot,
                                                          int32_t* __restrict__ slot_of_ent,
                                                          int32_t* __restrict__ group_off,
-                                                         int32_t* __restrict__ goffp,
                                                          int32_t* __restrict__ rowflag) {
   const int U = max(0, min(*n_S, cap));   // cap <= nvb * vbs is the capacity of S
   const int n_real = (U + vbs - 1) / vbs;
@@ -50,11 +49,9 @@ __global__ __launch_bounds__(256) void union_maps_kernel(const int32_t* __restri
   if (i >= (long long)n_real * T && i < (long long)n_real * T + kSlotPad) tok_of_slot[i] = 0;
   if (i < (long long)nvb * vbs) rowflag[i] = i < U ? 1 : 0;   // which compacted rows exist
   if (blockIdx.x == 0) {
-    const int Tp = (T + 63) & ~63;
     for (int g = threadIdx.x; g <= nvb; g += 256) {
       const int r = g < n_real ? g : n_real;
       group_off[g] = r * T;
-      goffp[g] = r * Tp;
     }
   }
 }
