@@ -31,10 +31,9 @@ constexpr int kSlotPad = 192;
 // the contraction is split `ksplit` ways over workgroups to fill the chip; split s writes its partial
 // scores to p + s*T*n_blocks and the top-e kernel adds the partials in a fixed order.
 struct ProbRouter {
-  static constexpr bool kBNC = false;
   static constexpr bool kAMC = false;
+  static constexpr bool kBNC = false;
   static constexpr bool kRowIdsInMemory = false;
-  static constexpr int kStoreBarriers = 0;
   const uint16_t* h; const uint16_t* Wg; float* p;
   int T, d, B, ksplit;
   __device__ bool locate(int wg, TileCoord& tc) const {
@@ -50,13 +49,13 @@ struct ProbRouter {
   __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
     return Wg + (size_t)(n < B ? n : B - 1) * d + (size_t)tc.aux * tc.nk * kTK;
   }
-  __device__ void store_rows(const TileCoord& tc, int r0, const float* rows, int tid) const {
-    float* dst = p + (size_t)tc.aux * T * B;
-    for (int idx = tid; idx < kEpiRows * kTN; idx += 256) {
-      const int r = idx / kTN, c = idx - r * kTN;
-      const int m = tc.m0 + r0 + r, n = tc.n0 + c;
-      if (m < T && n < B) dst[(size_t)m * B + n] = rows[tile_index(r, c)];
-    }
+  __device__ int out_cols(const TileCoord&) const { return B; }
+  static constexpr bool kAux = false;
+  __device__ int row_tag(const TileCoord&, int m) const { return m < T ? 1 : 0; }
+  __device__ size_t row_off(const TileCoord& tc, int, int m) const { return ((size_t)tc.aux * T + m) * B; }
+  __device__ void store2(size_t at, int n, float v0, float v1, uint32_t) const {
+    if (n < B) p[at] = v0;
+    if (n + 1 < B) p[at + 1] = v1;
   }
 };
 
@@ -70,10 +69,9 @@ constexpr int kTokScores = 0, kTokMasked = 1, kTokRelu = 2;
 
 template <int MODE>
 struct ProbTokKC {
+  static constexpr bool kAMC = false;
   static constexpr bool kBNC = false;
   static constexpr bool kRowIdsInMemory = false;
-  static constexpr bool kAMC = false;
-  static constexpr int kStoreBarriers = 0;
   const uint16_t* X;          // h (scores) or dOut (activation gradient), [T, d]
   const uint16_t* W;          // K or V, [N, d]
   const int32_t* perm; const int32_t* group_off;
@@ -81,7 +79,7 @@ struct ProbTokKC {
   int e, bs, bsp, d;
   float* sc;                  // kTokScores: [T*e, bs]
   const uint16_t* Ap;         // kTokMasked: A' [slots, bsp]
-  uint16_t* DS;               // kTokMasked / kTokRelu: [slots, bsp]
+  uint16_t* DS;               // kTokMasked / kTokRelu: [slots, bsp]; columns bs..bsp are written as zeros
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
     if (!locate_token_tile(sched, group_off, wg, (bs + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
@@ -95,59 +93,43 @@ struct ProbTokKC {
   __device__ const uint16_t* b_row(const TileCoord& tc, int n) const {
     return W + ((size_t)tc.g * bs + (n < bs ? n : bs - 1)) * d;
   }
-  __device__ void store_rows(const TileCoord& tc, int r0, float* rows, int tid) const {
+  __device__ int out_cols(const TileCoord&) const { return MODE == kTokScores ? bs : bsp; }
+  // scores: the row's entry number + 1; otherwise 1 for a row of the group
+  __device__ int row_tag(const TileCoord& tc, int m) const {
+    if (m >= tc.Mrows) return 0;
+    return MODE == kTokScores ? perm[tc.slot0 + m] + 1 : 1;
+  }
+  __device__ size_t row_off(const TileCoord& tc, int tag, int m) const {
+    return MODE == kTokScores ? (size_t)(tag - 1) * bs : (size_t)(tc.slot0 + m) * bsp;
+  }
+  // kTokMasked: the two activations of A' that decide whether the two gradient values are kept
+  static constexpr bool kAux = MODE == kTokMasked;
+  __device__ uint32_t load_aux(const TileCoord& tc, int m, int n) const {
+    const int mm = m < tc.Mrows ? m : tc.Mrows - 1, nn = n < bsp ? n : bsp - 2;
+    return *reinterpret_cast<const uint32_t*>(Ap + (size_t)(tc.slot0 + mm) * bsp + nn);
+  }
+  __device__ void store2(size_t at, int n, float v0, float v1, uint32_t mk) const {
     if constexpr (MODE == kTokScores) {
-      // a wave stores one row per step: 64 lanes x 4 floats = the 256 columns of the tile.  The row's entry id is
-      // wave-uniform and read through the constant address space (a scalar load).
-      const auto* cperm = as_const(perm);
-      const int c = (tid & 63) * 4, n = tc.n0 + c;
-      const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-#pragma unroll
-      for (int it = 0; it < kEpiRows / 4; ++it) {
-        const int r = w + it * 4;
-        const int m = tc.m0 + r0 + r;
-        if (m >= tc.Mrows) break;
-        float* dst = sc + (size_t)cperm[tc.slot0 + m] * bs + n;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
-        if ((bs & 3) == 0) {
-          if (n < bs) *reinterpret_cast<f32x4*>(dst) = v;
-        } else {
-          const float x[4] = {v.x, v.y, v.z, v.w};
-          for (int z = 0; z < 4; ++z)
-            if (n + z < bs) dst[z] = x[z];
-        }
+      if ((bs & 1) == 0) {   // rows are 8-byte aligned and n + 1 < bs whenever n < bs
+        if (n < bs) *reinterpret_cast<f32x2_hw*>(sc + at) = f32x2_hw{v0, v1};
+      } else {
+        if (n < bs) sc[at] = v0;
+        if (n + 1 < bs) sc[at + 1] = v1;
       }
     } else {
-      // slot-major: 8 columns per thread; mask by A' > 0 (or by sign), store DS'
-      const int c = (tid & 31) * 8, n = tc.n0 + c;
-#pragma unroll
-      for (int it = 0; it < kEpiRows / 8; ++it) {
-        const int r = (tid >> 5) + it * 8;
-        const int m = tc.m0 + r0 + r;
-        const bool row_in = m < tc.Mrows;
-        float x[8];
-        {
-          const f32x4 a = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c)]);
-          const f32x4 b = *reinterpret_cast<const f32x4*>(&rows[tile_index(r, c + 4)]);
-          x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-        }
-        if constexpr (MODE == kTokMasked) {
-          u32x4 mk = {0u, 0u, 0u, 0u};
-          if (row_in && n < bsp) mk = *reinterpret_cast<const u32x4*>(Ap + (size_t)(tc.slot0 + m) * bsp + n);
-          const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
-#pragma unroll
-          for (int z = 0; z < 8; ++z) {
-            const uint32_t a16 = (mw[z >> 1] >> (16 * (z & 1))) & 0xFFFFu;
-            const bool on = (a16 & 0x7FFFu) != 0u && (a16 & 0x8000u) == 0u;   // positive, non-zero activation
-            x[z] = on ? x[z] : 0.f;
-          }
-        } else {
-          // rows beyond the group and columns beyond the block (computed from clamped operand rows) are zero
-#pragma unroll
-          for (int z = 0; z < 8; ++z) x[z] = (row_in && n + z < bs && x[z] > 0.f) ? x[z] : 0.f;
-        }
-        if (row_in && n < bsp) Vec8<bf16_t>::store(reinterpret_cast<bf16_t*>(DS) + (size_t)(tc.slot0 + m) * bsp + n, x);
+      if (n >= bsp) return;   // bsp is even: n + 1 < bsp
+      if constexpr (MODE == kTokMasked) {
+        // keep the gradient where the activation is positive (A' holds zeros in the columns bs..bsp)
+        const bool on0 = (mk & 0x7FFFu) != 0u && (mk & 0x8000u) == 0u;
+        const bool on1 = (mk & 0x7FFF0000u) != 0u && (mk & 0x80000000u) == 0u;
+        v0 = on0 ? v0 : 0.f;
+        v1 = on1 ? v1 : 0.f;
+      } else {
+        // columns beyond the block (computed from clamped operand rows) are zero
+        v0 = (n < bs && v0 > 0.f) ? v0 : 0.f;
+        v1 = (n + 1 < bs && v1 > 0.f) ? v1 : 0.f;
       }
+      *reinterpret_cast<uint32_t*>(DS + at) = pack_bf16x2(v0, v1);
     }
   }
 };
@@ -155,8 +137,8 @@ struct ProbTokKC {
 // Token-major, B contiguous along n: part[slot, :] = A[slot, 0:bs] . W_b   (W = V: forward value sum;
 // W = K: dh).  A is slot-major [slots, bsp] with zero padding in columns bs..bsp.
 struct ProbTokNC {
-  static constexpr bool kBNC = true;
   static constexpr bool kAMC = false;
+  static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = false;
   const uint16_t* A;          // A' or DS'
   const uint16_t* W;          // V or K, [N, d]
@@ -175,8 +157,13 @@ struct ProbTokNC {
   }
   __device__ int b_row_ids(const TileCoord& tc, int k) const { return tc.g * bs + (k < bs ? k : bs - 1); }
   __device__ const uint16_t* b_row_ptr(int row) const { return W + (size_t)row * d; }
-  __device__ uint16_t* out_base(const TileCoord& tc) const { return part + (size_t)tc.slot0 * d; }
-  __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < tc.Mrows; }
+  __device__ int out_cols(const TileCoord&) const { return d; }   // d % 64 == 0
+  static constexpr bool kAux = false;
+  __device__ int row_tag(const TileCoord& tc, int m) const { return m < tc.Mrows ? 1 : 0; }
+  __device__ size_t row_off(const TileCoord& tc, int, int m) const { return (size_t)(tc.slot0 + m) * d; }
+  __device__ void store2(size_t at, int, float v0, float v1, uint32_t) const {
+    *reinterpret_cast<uint32_t*>(part + at) = pack_bf16x2(v0, v1);
+  }
 };
 
 // Neuron-major, both operands indexed by the contraction index (slot) in their rows:
@@ -185,8 +172,8 @@ struct ProbTokNC {
 // so no transposed copy of the activations exists.  The contraction length is padded to 64: the padding rows of A
 // come from a row of zeros, those of X are any valid rows.  Only rows whose neuron is touched are written.
 struct ProbNeuTN {
-  static constexpr bool kBNC = true;
   static constexpr bool kAMC = true;
+  static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = true;
   const uint16_t* A;          // [slots, bsp]
   const uint16_t* zrow;       // bsp zeros
@@ -216,8 +203,15 @@ struct ProbNeuTN {
   // tok_of_slot is padded by kSlotPad valid entries, which covers the padded contraction length
   __device__ const int32_t* b_row_id_src(const TileCoord& tc, int k0) const { return tok_of_slot + tc.slot0 + k0; }
   __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }
-  __device__ uint16_t* out_base(const TileCoord& tc) const { return G + (size_t)tc.g * bs * d; }
-  __device__ bool out_row_ok(const TileCoord& tc, int m) const { return m < bs && flag[(size_t)tc.g * bs + m] > 0; }
+  __device__ int out_cols(const TileCoord&) const { return d; }   // d % 64 == 0
+  __device__ int row_tag(const TileCoord& tc, int m) const {
+    return (m < bs && flag[(size_t)tc.g * bs + m] > 0) ? 1 : 0;
+  }
+  static constexpr bool kAux = false;
+  __device__ size_t row_off(const TileCoord& tc, int, int m) const { return ((size_t)tc.g * bs + m) * d; }
+  __device__ void store2(size_t at, int, float v0, float v1, uint32_t) const {
+    *reinterpret_cast<uint32_t*>(G + at) = pack_bf16x2(v0, v1);
+  }
 };
 
 // ---- helper kernels ----------------------------------------------------------------------------

@@ -1,30 +1,45 @@
 // Grouped bf16 GEMM core for gfx950 matrix cores, shared by every dense contraction of the layer:
 //
-//   C[m, n] = sum_k A[m, k] * B(k, n)          fp32 accumulation, v_mfma_f32_32x32x16_bf16
+//   C[m, n] = sum_k A(m, k) * B(k, n)          fp32 accumulation, v_mfma_f32_32x32x16_bf16
 //
-// A is always contiguous along k.  B is either contiguous along k ("KC": rows indexed by n, used for
-// the router and key scores, Eq. 5 / Eq. 6, and for dOut.V^T in the backward) or contiguous along n
-// ("NC": rows indexed by k, used where the contraction runs over neurons or tokens: the value sum of
-// Eq. 4, dh, dK, dV).  This file holds what both layouts share and the kernel of the KC problems, whose
-// outputs need a pass through LDS (fp32 scores scattered by entry, masked activations in two layouts);
-// gemm_stream.h holds the kernel of the NC problems.
+// Each operand is contiguous either along the contraction index or along its own index:
+//   A k-contiguous (rows indexed by m) / B k-contiguous (rows indexed by n): router and key scores (Eq. 5, Eq. 6)
+//     and dOut . V^T in the backward;
+//   B n-contiguous (rows indexed by k): where the contraction runs over neurons or tokens while the rows of V, K,
+//     dOut, h are contiguous in d: the value sum of Eq. 4, dh, dK, dV;
+//   A m-contiguous (rows indexed by k): dK, dV, whose A operand is the slot-major activation matrix, read as it is.
 //
-// Tile 128 (m) x 256 (n) x 64 (k), 4 compute waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles, plus
-// loader waves.  Operands go global -> LDS directly (global_load_lds, 16 B per lane), three stages of
-// 48 KB in a ring with one barrier per k tile; the wait for a stage is a partial vmcnt so that the next
-// stage's loads stay in flight.  LDS layouts are XOR-swizzled so that both the linear DMA writes
-// and the fragment reads are free of bank conflicts:
+// Tile 128 (m) x 256 (n) x 64 (k); 4 compute waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles, plus two
+// loader waves that own the whole global -> LDS traffic (global_load_lds, 16 B per lane).  Three stages of 48 KB
+// form a ring.  LDS layouts are XOR-swizzled so that both the linear DMA writes and the fragment reads are free of
+// bank conflicts:
 //   k-contiguous operand: rows of 64 k = 8 chunks of 16 B; logical chunk c of row r sits at chunk
 //     c ^ ((r >> 1) & 7); fragments are read with ds_read_b128.
-//   n-contiguous operand: rows of 256 n = 32 chunks of 16 B; logical chunk c of row k sits at chunk
-//     c ^ (2 * (k & 7)); fragments are read with the transposing ds_read_b64_tr_b16, which hands
-//     lane i of a 16-lane group the four k-consecutive values of column i of a 4 x 16 block.
+//   n-contiguous B: rows of 256 n = 32 chunks; logical chunk c of row k sits at chunk c ^ (2 * (k & 7));
+//   m-contiguous A: rows of 128 m = 16 chunks; logical chunk c of row k sits at chunk c ^ (4 * (k & 3));
+//     both are read with the transposing ds_read_b64_tr_b16, which hands lane i of a 16-lane group the four
+//     k-consecutive values of column i of a 4 x 16 block.
+//
+// The k tiles of all the tiles a workgroup works through form ONE stream through the ring: the loaders request
+// stream position s + 2 right after the barrier that hands position s to the compute waves, whether or not s + 2
+// belongs to the next output tile, so the operand pipeline never drains at a tile boundary.  There is exactly one
+// workgroup barrier per k tile of the stream, executed by all six waves.  (An extra barrier at the end of every
+// tile, releasing its last stage before the stores so that the loaders request a third k tile during the epilogue,
+// was measured and did not pay.)
+//
+// The epilogue needs neither LDS nor barriers: neighbouring lanes exchange one accumulator value through a DPP
+// move, so that every lane holds two adjacent columns of one row, and hands them to the policy, which converts and
+// stores them (4 bytes of bf16 or 8 bytes of fp32 per lane; a half wave writes 64 or 128 contiguous bytes of each
+// of two rows per instruction).  While the compute waves store, the loaders are already two k tiles into the next
+// tile.
 //
 // Workgroups are mapped to tiles XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs,
 // so workgroup id w works for XCD w % 8, and all tiles of one group (block of neurons) are given to
 // one XCD, consecutively, so that the group's operand panels are fetched from HBM once and shared in
 // that XCD's L2.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 namespace meft {
@@ -35,11 +50,11 @@ constexpr int kOperandLdsBytes = kStages * kStageElems * 2;    // 144 KB
 constexpr int kIdRingSlots = 4;                                // k tiles of gathered-row numbers kept per loader
 constexpr int kGemmLdsBytes = kOperandLdsBytes + 2 * kIdRingSlots * 64 * 4;   // + 2 KB
 constexpr int kXcd = 8;
+constexpr int kLoaders = 2;    // waves that only request operands (the other four only compute)
+constexpr int kGemmThreads = 256 + 64 * kLoaders;
 
 #define MEFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define MEFT_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
-
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 
 // Read-only index arrays are read through the constant address space where the index is wave-uniform: that
 // makes the load a scalar load, which is counted apart from the vector loads that pace the operand pipeline
@@ -60,27 +75,39 @@ struct TileCoord {
 };
 
 // A problem policy P provides:
-//   static constexpr bool kBNC;                         B contiguous along n?
 //   __device__ bool locate(int wg, TileCoord&) const;   false: no tile with id wg, nor with any larger id on
 //                                                       the same XCD (ids wg + 8, wg + 16, ...)
-//   __device__ const uint16_t* a_row(const TileCoord&, int m) const;   start of row m (clamped by the policy)
-// and, for the kernel in this file (KC):
-//   __device__ const uint16_t* b_row(const TileCoord&, int n) const;   start of B row n (clamped)
-//   __device__ void store_rows(const TileCoord&, int r0, float* rows, int tid) const;   write tile rows r0..r0+31;
-//       executed by the 256 compute threads (tid 0..255); any workgroup barrier inside must be MEFT_BARRIER_LDS()
-//   static constexpr int kStoreBarriers;                number of such barriers in one store_rows call
-// (gemm_stream.h lists what an NC policy provides instead.)
-//
-// acc[i][j][r] of a wave holds C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4,
-// n = wn + j*32 + lane%32 (tile-local); the kernel lays 32 rows at a time out row-major in LDS (tile_index with
-// the row counted from the pass start) and hands them to store_rows, which all 256 threads execute.  Global
-// loads inside store_rows make the compiler wait for every outstanding vector-memory operation, including
-// the next tile's operand loads; policies therefore read per-row indices with scalar loads where they can.
+//   static constexpr bool kAMC;                         A contiguous along m (rows indexed by k)?
+//       false: __device__ const uint16_t* a_row(const TileCoord&, int m) const;    start of row m (clamped)
+//       true:  __device__ const uint16_t* a_krow(const TileCoord&, int k) const;   start of the row that holds
+//              contraction index k (a row of zeros beyond the contraction length), and
+//              __device__ int a_cols(const TileCoord&) const;                      its length (a multiple of 8)
+//   static constexpr bool kBNC;                         B contiguous along n (rows indexed by k)?
+//       false: __device__ const uint16_t* b_row(const TileCoord&, int n) const;    start of B row n (clamped)
+//       true:  __device__ const uint16_t* b_row_ptr(int row) const;   start of B row `row`; rows are
+//              TileCoord::Ncols elements apart;  and, with static constexpr bool kRowIdsInMemory (false where B
+//              is k-contiguous),
+//         false: __device__ int b_row_ids(const TileCoord&, int k) const;  number of the B row that holds k (plain
+//                arithmetic, no memory access), any valid row for k beyond the contraction length;
+//         true:  __device__ const int32_t* b_row_id_src(const TileCoord&, int k0) const;  where the numbers of the B
+//                rows of k0 .. k0 + 63 are stored (valid rows also beyond the contraction length: those products are
+//                zero); called for k0 = 0, 64, ... below 64 * nk.  The numbers travel like the operands: a
+//                4-byte-per-lane global -> LDS load puts the 64 numbers of a k tile into a small ring in LDS one
+//                position ahead of the operand request that uses them;
+//   __device__ int out_cols(const TileCoord&) const;    columns of the group's output that are stored
+//   __device__ int row_tag(const TileCoord&, int m) const;   0: row m of the group's output is not stored (also for
+//                m beyond the group's rows); anything else is handed back to row_off.  May read memory: it is asked
+//                before the k loop.
+//   __device__ size_t row_off(const TileCoord&, int tag, int m) const;   element offset of (row m, column 0) in
+//                the output array
+//   __device__ void store2(size_t at, int n, float v0, float v1, uint32_t aux) const;   store C[m][n] = v0 and
+//                C[m][n + 1] = v1 at element offset `at` (= row_off + n; n even, n < round-up of out_cols to 32; the
+//                policy checks n and n + 1 against out_cols where that is not a multiple of 32)
+//   static constexpr bool kAux;  true: __device__ uint32_t load_aux(const TileCoord&, int m, int n) const;   a word
+//                the policy wants next to the two values of (m, n), e.g. a mask; called for every position of the
+//                tile, stored or not, so the policy clamps m and n to valid ones
 
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-// index of element (m, n) of an epilogue pass in LDS, m counted from the first row of the pass
-__device__ __forceinline__ int tile_index(int m, int n) { return m * kTN + (n ^ (((m >> 2) & 1) << 7)); }
 
 // Eight transposing LDS reads (the four n-contiguous B fragments of one k16 step, low and high k half)
 // followed by the wait for them.  Written as one asm block: issued through the builtin, the compiler
@@ -105,175 +132,381 @@ __device__ __forceinline__ void tr_read8(u32x2 (&o)[8], const uint32_t (&alo)[4]
       : "memory");
 }
 
-constexpr int kEpiRows = 32;   // rows of the output tile staged through LDS per epilogue pass
-constexpr int kLoaders = 2;    // waves that only request operands (the other four only compute)
-constexpr int kGemmThreads = 256 + 64 * kLoaders;
+// Twelve transposing LDS reads of one k16 step (the two m-contiguous A fragments and the four n-contiguous B
+// fragments, low and high k half each) followed by the wait for them.  xa = {A0 low, A0 high, A1 low, A1 high}.
+template <int OFFA, int OFFB>
+__device__ __forceinline__ void tr_read12(u32x2 (&oa)[4], u32x2 (&ob)[8], const uint32_t (&xa)[4],
+                                          const uint32_t (&blo)[4], const uint32_t (&bhi)[4]) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %12 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %1, %13 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %2, %14 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %3, %15 offset:%24\n\t"
+      "ds_read_b64_tr_b16 %4, %16 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %5, %17 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %6, %18 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %7, %19 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %8, %20 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %9, %21 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %10, %22 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %11, %23 offset:%25\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(oa[0]), "=&v"(oa[1]), "=&v"(oa[2]), "=&v"(oa[3]), "=&v"(ob[0]), "=&v"(ob[1]), "=&v"(ob[2]),
+        "=&v"(ob[3]), "=&v"(ob[4]), "=&v"(ob[5]), "=&v"(ob[6]), "=&v"(ob[7])
+      : "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]), "v"(blo[0]), "v"(bhi[0]), "v"(blo[1]), "v"(bhi[1]),
+        "v"(blo[2]), "v"(bhi[2]), "v"(blo[3]), "v"(bhi[3]), "n"(OFFA), "n"(OFFB)
+      : "memory");
+}
 
-// Workgroup barrier for the kernel below.  All six waves execute the same sequence of barriers; a compute wave
-// first waits for its own LDS traffic, a loader wave for the operand loads that have to have landed.
+// Workgroup barrier of a compute wave: it first waits for its own LDS traffic.  (A loader wave waits for the
+// operand loads that have to have landed instead.)
 #define MEFT_BARRIER_LDS() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
 // Four compute waves (tid 0..255) and kLoaders loader waves.  The loaders own the whole global -> LDS traffic:
 // measured on gfx950 the operand path, not the matrix cores or LDS, bounds these contractions (a compute unit keeps
 // about a hundred 128-byte read requests in flight, no more), and a wave that both requests operands and issues
 // MFMAs keeps neither queue full.  The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ...
-// (gridDim.x is a multiple of 8, so it stays on one XCD's list); the first two operand stages of the next tile are
-// requested before the epilogue of the current one.
+// (gridDim.x is a multiple of 8, so it stays on one XCD's list).
 template <class P>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
-  static_assert(!P::kBNC, "n-contiguous B operands go through gemm_stream_kernel");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // locate() answers false only when the workgroup's XCD has no tile with this or any larger id
-  auto next_tile = [&](int& wg, TileCoord& t) -> bool { return wg < n_tiles_bound && p.locate(wg, t); };
-  constexpr int kPasses = kTM / kEpiRows;
+  auto next_tile = [&](int wg, TileCoord& t) -> bool { return wg < n_tiles_bound && p.locate(wg, t); };
+  const int step = gridDim.x;
 
-  int wg = blockIdx.x;
   TileCoord tc;
-  if (!next_tile(wg, tc)) return;   // the same answer in every wave
+  if (!next_tile(blockIdx.x, tc)) return;   // the same answer in every wave
 
   if (wave >= 4) {
     // ------------------------------------------------------------------ loader waves
     const int lw = wave - 4;
-    constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (8 rows x 128 B) per loader and stage: 8
-    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (8 rows x 128 B) per loader and stage: 16
+    constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (1 KB each) per loader and stage: 8
+    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (1 KB each) per loader and stage: 16
     static_assert(LA + LB <= 63, "partial vmcnt wait out of range");
-    struct Loads {
-      const uint16_t* pa[LA];
-      const uint16_t* pb[LB];
-    };
     const int lr8 = lane >> 3;
-    auto setup = [&](Loads& L, const TileCoord& t) {
+    int* idring = reinterpret_cast<int*>(smem + kOperandLdsBytes / 2) + lw * kIdRingSlots * 64;
+
+    // Three cursors walk the same sequence of (tile, k tile) pairs: the row numbers of gathered B rows are
+    // requested three positions ahead of the barrier, the operands two positions ahead.
+    //   consume: position handed to the compute waves at the next barrier
+    int wg_c = blockIdx.x, nk_c = tc.nk;
+    //   operands
+    int wg_o = blockIdx.x, k_o = 0, n_o = 0, stage_o = 0;
+    bool ok_o = true;
+    TileCoord t_o = tc;
+    //   row numbers (only where they sit in memory)
+    int wg_d = blockIdx.x, k_d = 0, n_d = 0;
+    bool ok_d = P::kBNC && P::kRowIdsInMemory;
+    TileCoord t_d = tc;
+
+    // A, k-contiguous: a wave-load covers 8 rows (m) x 128 bytes; fixed row pointers per tile, advanced by k.
+    // A, m-contiguous: a wave-load covers 4 rows (k) x 256 bytes; lane l fetches the 16-byte chunk
+    //   (l & 15) ^ (4 * (row & 3)) of its row (the LDS swizzle; row & 3 == (l >> 4) & 3 for every load), so one
+    //   column offset per tile serves all the loads.
+    // B, k-contiguous: like A, 8 rows (n) x 128 bytes.
+    // B, n-contiguous: a wave-load covers two k rows (lanes 0..31 the even one, lanes 32..63 the odd one), 512 bytes
+    //   of each; lane l fetches the chunk (l & 31) ^ (2 * (row & 7)); row & 7 only depends on i & 3, so four
+    //   column offsets per tile cover all the loads.
+    const uint16_t* pa[P::kAMC ? 1 : LA];
+    int acol = 0;
+    const uint16_t* pb[P::kBNC ? 4 : LB];
+    const int half = lane >> 5;
+    auto setup = [&]() {
+      if constexpr (P::kAMC) {
+        const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
+        const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
+        acol = col > last ? last : col;                                 // clamp (rows beyond Mrows are never stored)
+      } else {
 #pragma unroll
-      for (int i = 0; i < LA; ++i) {
-        const int row = (lw * LA + i) * 8 + lr8;
-        L.pa[i] = p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        for (int i = 0; i < LA; ++i) {
+          const int row = (lw * LA + i) * 8 + lr8;
+          pa[i] = p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        }
       }
+      if constexpr (P::kBNC) {
 #pragma unroll
-      for (int i = 0; i < LB; ++i) {
-        const int row = (lw * LB + i) * 8 + lr8;
-        L.pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        for (int q = 0; q < 4; ++q) {
+          const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
+          int col = t_o.n0 + chunk * 8;
+          col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;              // clamp (columns beyond Ncols are never stored)
+          pb[q] = p.b_row_ptr(0) + col;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+          const int row = (lw * LB + i) * 8 + lr8;
+          pb[i] = p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        }
       }
-    };
-    auto issue = [&](const Loads& L, int kt, int stage) {
-      uint16_t* sa = smem + stage * kStageElems;
-      uint16_t* sb = sa + kTM * kTK;
-#pragma unroll
-      for (int i = 0; i < LA; ++i)
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pa[i] + kt * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LB; ++i)
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(L.pb[i] + kt * kTK), MEFT_LPTR(sb + (lw * LB + i) * 8 * kTK), 16, 0, 0);
     };
 
-    // requests the first kStages - 1 k tiles of a tile
-    auto prologue = [&](const Loads& L, const TileCoord& t) {
-#pragma unroll
-      for (int s = 0; s < kStages - 1; ++s)
-        if (s < t.nk) issue(L, s, s);
-    };
-    Loads cur;
-    setup(cur, tc);
-    prologue(cur, tc);
-    for (;;) {
-      const int nk = tc.nk;
-      int stage = 0;
-      bool more = false;
-      TileCoord tn;
-      Loads nxt;
-      for (int kt = 0; kt < nk; ++kt) {
-        // k tile kt has landed once at most LA + LB younger loads of this wave are outstanding (the counter retires
-        // in issue order); with no younger k tile requested, everything is awaited
-        if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        if (kt + kStages - 1 < nk) {
-          int ps = stage - 1;
-          if (ps < 0) ps += kStages;
-          issue(cur, kt + kStages - 1, ps);                // the buffer of k tile kt-1: every compute wave is past it
-        }
-        if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }
-        if (kt == nk - 1 && more) setup(nxt, tn);
-        stage = stage + 1 == kStages ? 0 : stage + 1;
+    auto request_ids = [&]() {
+      if constexpr (P::kBNC && P::kRowIdsInMemory) {
+        if (!ok_d) return;
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(p.b_row_id_src(t_d, k_d * kTK) + lane),
+                                         MEFT_LPTR(idring + (n_d & (kIdRingSlots - 1)) * 64), 4, 0, 0);
+        ++n_d;
+        if (++k_d == t_d.nk) { wg_d += step; k_d = 0; ok_d = next_tile(wg_d, t_d); }
       }
-      MEFT_BARRIER_LDS();   // every compute wave is done reading operand stages
-      if (more) prologue(nxt, tn);
-      // the epilogue's barriers (two per pass plus those inside the policy's store_rows)
+    };
+    auto request_operands = [&]() {
+      if (!ok_o) return;
+      uint16_t* sa = smem + stage_o * kStageElems;
+      uint16_t* sb = sa + kTM * kTK;
+      // n-contiguous B: ids[i] = number of the B row this lane fetches in its i-th load,
+      // k = 64 * k_o + 2 * (lw * LB + i) + half
+      int ids[LB];
+      if constexpr (P::kBNC && P::kRowIdsInMemory) {
+        // out of the ring; one asm block with its own wait (through plain loads the compiler would first drain every
+        // outstanding operand load)
+        const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(
+            idring + (n_o & (kIdRingSlots - 1)) * 64 + 2 * lw * LB + half);
+        static_assert(LB == 16, "the block below reads sixteen row numbers");
+        asm volatile(
+            "ds_read_b32 %0, %16\n\tds_read_b32 %1, %16 offset:8\n\tds_read_b32 %2, %16 offset:16\n\t"
+            "ds_read_b32 %3, %16 offset:24\n\tds_read_b32 %4, %16 offset:32\n\tds_read_b32 %5, %16 offset:40\n\t"
+            "ds_read_b32 %6, %16 offset:48\n\tds_read_b32 %7, %16 offset:56\n\tds_read_b32 %8, %16 offset:64\n\t"
+            "ds_read_b32 %9, %16 offset:72\n\tds_read_b32 %10, %16 offset:80\n\tds_read_b32 %11, %16 offset:88\n\t"
+            "ds_read_b32 %12, %16 offset:96\n\tds_read_b32 %13, %16 offset:104\n\tds_read_b32 %14, %16 offset:112\n\t"
+            "ds_read_b32 %15, %16 offset:120\n\ts_waitcnt lgkmcnt(0)"
+            : "=&v"(ids[0]), "=&v"(ids[1]), "=&v"(ids[2]), "=&v"(ids[3]), "=&v"(ids[4]), "=&v"(ids[5]), "=&v"(ids[6]),
+              "=&v"(ids[7]), "=&v"(ids[8]), "=&v"(ids[9]), "=&v"(ids[10]), "=&v"(ids[11]), "=&v"(ids[12]),
+              "=&v"(ids[13]), "=&v"(ids[14]), "=&v"(ids[15])
+            : "v"(a)
+            : "memory");
+      } else if constexpr (P::kBNC) {
 #pragma unroll
-      for (int b = 0; b < kPasses * (2 + P::kStoreBarriers); ++b) MEFT_BARRIER_LDS();
-      if (!more) return;
-      tc = tn;
-      cur = nxt;
+        for (int i = 0; i < LB; ++i) ids[i] = p.b_row_ids(t_o, k_o * kTK + 2 * (lw * LB + i) + half);
+      }
+#pragma unroll
+      for (int i = 0; i < LA; ++i) {
+        if constexpr (P::kAMC) {
+          const uint16_t* src = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4)) + acol;
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sa + (lw * LA + i) * 4 * kTM), 16, 0, 0);
+        } else {
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + k_o * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
+        }
+      }
+      if constexpr (P::kBNC) {
+        const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+          const char* src = reinterpret_cast<const char*>(pb[i & 3]) + (uint64_t)(uint32_t)ids[i] * row_bytes;
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (lw * LB + i) * 512), 16, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < LB; ++i)
+          __builtin_amdgcn_global_load_lds(MEFT_GPTR(pb[i] + k_o * kTK), MEFT_LPTR(sb + (lw * LB + i) * 8 * kTK), 16, 0, 0);
+      }
+      ++n_o;
+      stage_o = stage_o + 1 == kStages ? 0 : stage_o + 1;
+      if (++k_o == t_o.nk) {
+        wg_o += step; k_o = 0; ok_o = next_tile(wg_o, t_o);
+        if (ok_o) setup();
+      }
+    };
+
+    setup();
+    if constexpr (P::kBNC && P::kRowIdsInMemory) {
+#pragma unroll
+      for (int s = 0; s < kStages; ++s) request_ids();
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+#pragma unroll
+    for (int s = 0; s < kStages - 1; ++s) request_operands();
+
+    int n_c = 0;   // positions handed over so far
+    for (;;) {
+      for (int kt = 0; kt < nk_c; ++kt) {
+        // position n_c has landed once at most the LA + LB loads of position n_c + 1 are outstanding (the counter
+        // retires in issue order, and the row numbers of a later position are requested before those loads); with
+        // nothing requested beyond n_c, everything is awaited
+        if (n_o > n_c + 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        // every compute wave is past position n_c - 1: its stage takes position n_c + 2
+        request_ids();
+        request_operands();
+        ++n_c;
+      }
+      wg_c += step;
+      TileCoord t;
+      if (!next_tile(wg_c, t)) return;
+      nk_c = t.nk;
     }
   }
 
   // -------------------------------------------------------------------- compute waves
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
   const int fr = lane & 31, fc = lane >> 5;
-  int offA[2], keyA[2];
+  // k-contiguous operands: element offsets of this lane's fragment rows inside a stage, and their swizzle keys
+  int offA[2], keyA[2], offB[4], keyB[4];
 #pragma unroll
   for (int i = 0; i < 2; ++i) { const int r = wm + i * 32 + fr; offA[i] = r * kTK; keyA[i] = (r >> 1) & 7; }
-  int offB[4], keyB[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) { const int r = wn + j * 32 + fr; offB[j] = kTM * kTK + r * kTK; keyB[j] = (r >> 1) & 7; }
+  // m- / n-contiguous operands: LDS byte offsets (A: inside a stage, B: inside its B region) of this lane's
+  // transposing reads.  Lane s of a 16-lane group points at row (k base + s/4), columns 4*(s%4)..+3 of a 4 x 16
+  // block and receives column s of that block, four consecutive k.  Low half: k = 8*(lane/32) + 0..3, high half +4.
+  uint32_t tra_lo[2], tra_hi[2], tr_lo[4], tr_hi[4];
+  {
+    const int gq = lane >> 4, s = lane & 15;
+    const int k_lo = 8 * (gq >> 1) + (s >> 2), k_hi = k_lo + 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int m = wm + i * 32 + 16 * (gq & 1) + 4 * (s & 3);
+      tra_lo[i] = (uint32_t)(k_lo * kTM + (((m >> 3) ^ (4 * (k_lo & 3))) << 3) + (m & 7)) * 2u;
+      tra_hi[i] = (uint32_t)(k_hi * kTM + (((m >> 3) ^ (4 * (k_hi & 3))) << 3) + (m & 7)) * 2u;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = wn + j * 32 + 16 * (gq & 1) + 4 * (s & 3);
+      tr_lo[j] = (uint32_t)(k_lo * kTN + (((n >> 3) ^ (2 * (k_lo & 7))) << 3) + (n & 7)) * 2u;
+      tr_hi[j] = (uint32_t)(k_hi * kTN + (((n >> 3) ^ (2 * (k_hi & 7))) << 3) + (n & 7)) * 2u;
+    }
+  }
 
+  int wg = blockIdx.x;
+  int stage = 0;   // runs on across tiles, like the loaders' stage_o
   for (;;) {
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // lane l: the tag of row wm + l of this tile.  Asked before the k loop, so that a policy's memory read has long
+    // returned when the answer is needed.
+    const int my_tag = p.row_tag(tc, tc.m0 + wm + lane);
 
+    f32x16 acc[2][4];
     const int nk = tc.nk;
-    int stage = 0;
     bool more = false;
     TileCoord tn;
-    for (int kt = 0; kt < nk; ++kt) {
-      MEFT_BARRIER_LDS();   // the loaders have seen k tile kt land
-      if (kt == 0) { wg += gridDim.x; more = next_tile(wg, tn); }
+    // one k tile out of stage `stage`; kFirst: the first k16 step starts from zero instead of from acc (the matrix
+    // instruction takes the constant as its addend, so the accumulators are never cleared by hand)
+    auto k_tile = [&](auto first_tag) {
+      constexpr bool kFirst = decltype(first_tag)::value;
       const uint16_t* st = smem + stage * kStageElems;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         bf16x8 fa[2], fb[4];
-        const int c = ks * 2 + fc;
+        const int c = ks * 2 + fc;   // k-contiguous operands: this lane's 16-byte chunk of the k16 step
+        if constexpr (!P::kAMC) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
+          for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
+        }
+        if constexpr (!P::kBNC) {
+          static_assert(!P::kAMC || P::kBNC, "an m-contiguous A comes with an n-contiguous B");
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
+          for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
+        } else {
+          // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 bytes); that changes neither
+          // (k & 7) nor (k & 3), so the swizzles hold
+          const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
+          uint32_t alo[4], ahi[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
+          u32x2 o[8];
+          if constexpr (P::kAMC) {
+            const uint32_t abase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st);
+            const uint32_t xa[4] = {abase + tra_lo[0], abase + tra_hi[0], abase + tra_lo[1], abase + tra_hi[1]};
+            u32x2 oa[4];
+            if (ks == 0) tr_read12<0, 0>(oa, o, xa, alo, ahi);
+            else if (ks == 1) tr_read12<4096, 8192>(oa, o, xa, alo, ahi);
+            else if (ks == 2) tr_read12<8192, 16384>(oa, o, xa, alo, ahi);
+            else tr_read12<12288, 24576>(oa, o, xa, alo, ahi);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+              const u32x4 w = {oa[2 * i].x, oa[2 * i].y, oa[2 * i + 1].x, oa[2 * i + 1].y};
+              fa[i] = __builtin_bit_cast(bf16x8, w);
+            }
+          } else {
+            if (ks == 0) tr_read8<0>(o, alo, ahi);
+            else if (ks == 1) tr_read8<8192>(o, alo, ahi);
+            else if (ks == 2) tr_read8<16384>(o, alo, ahi);
+            else tr_read8<24576>(o, alo, ahi);
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
+            fb[j] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          for (int j = 0; j < 4; ++j) {
+            if (kFirst && ks == 0) {
+              const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], zero, 0, 0, 0);
+            } else {
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+          }
       }
       stage = stage + 1 == kStages ? 0 : stage + 1;
+    };
+    MEFT_BARRIER_LDS();   // the loaders have seen the tile's first k tile land
+    wg += step;
+    more = next_tile(wg, tn);
+    k_tile(std::true_type{});
+    for (int kt = 1; kt < nk; ++kt) {
+      MEFT_BARRIER_LDS();
+      k_tile(std::false_type{});
     }
 
-    MEFT_BARRIER_LDS();   // every compute wave is done reading operand stages; the loaders go on with the next tile
-
-    // ---- epilogue: the fp32 tile goes through the LDS region of stage 2, kEpiRows rows at a time, so that the
-    // policy can store whole rows with 16-byte accesses.  Layout of a pass: row-major, 256 floats per row, the
-    // two 128-float halves of a row swapped when (row >> 2) is odd (keeps the half-waves of one accumulator
-    // write in different banks).  Rows 32*pass .. +31 belong to the waves with wm == 64*(pass/2), fragment pass%2.
-    float* tile = reinterpret_cast<float*>(smem + (kStages - 1) * kStageElems);
+    // ---- epilogue, out of the registers.  acc[i][j][r] is C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4
+    // and n = wn + j*32 + lane%32.  For a register pair (r, r+1), r even, an even lane (column c) keeps its value of
+    // row m and takes its right neighbour's value of that row; the odd lane (column c+1) keeps its value of row m+1
+    // and takes its left neighbour's (DPP quad_perm [1,0,3,2] swaps neighbours).  Both then hold columns (c, c+1) of
+    // one row.  Per half of the accumulators (i) the rows' tags and whatever the policy reads per element (load_aux:
+    // unconditional loads, all in flight together) are fetched first, then the values are exchanged and stored.
+    {
+      const bool odd = (lane & 1) != 0;
+      const int nj = (p.out_cols(tc) - (tc.n0 + wn) + 31) / 32;   // 32-column fragments of this wave with stored columns
+      const int ncol = tc.n0 + wn + (fr & ~1);
 #pragma unroll
-    for (int pass = 0; pass < kPasses; ++pass) {
-      if ((wave >> 1) == (pass >> 1)) {
+      for (int i = 0; i < 2; ++i) {
+        int tag[8];
+        uint32_t aux[8][4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int n = wn + j * 32 + fr;
+        for (int q = 0; q < 8; ++q) {
+          const int r = 2 * q;
+          const int rl = i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3) + (lane & 1);    // row inside the wave's 64
+          tag[q] = __builtin_amdgcn_ds_bpermute(rl << 2, my_tag);
+          if constexpr (P::kAux) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int ml = (r >> 2) * 8 + fc * 4 + (r & 3);
-            tile[tile_index(ml, n)] = acc[pass & 1][j][r];
+            for (int j = 0; j < 4; ++j) aux[q][j] = p.load_aux(tc, tc.m0 + wm + rl, ncol + 32 * j);
+          } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) aux[q][j] = 0u;
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const int r = 2 * q;
+          const int rl = i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3) + (lane & 1);
+          float lo[4], hi[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
+            const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
+            const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
+            lo[j] = odd ? bn : a;
+            hi[j] = odd ? b : an;
+          }
+          if (tag[q] != 0) {
+            const size_t at = p.row_off(tc, tag[q], tc.m0 + wm + rl) + ncol;
+            if (nj >= 4) {
+              p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
+              p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
+              p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
+              p.store2(at + 96, ncol + 96, lo[3], hi[3], aux[q][3]);
+            } else {
+              if (nj > 0) p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
+              if (nj > 1) p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
+              if (nj > 2) p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
+            }
           }
         }
       }
-      MEFT_BARRIER_LDS();
-      p.store_rows(tc, pass * kEpiRows, tile, tid);   // contains P::kStoreBarriers workgroup barriers
-      MEFT_BARRIER_LDS();
     }
     if (!more) break;
     tc = tn;

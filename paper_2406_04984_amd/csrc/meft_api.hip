@@ -15,7 +15,6 @@
 #include "dense_path.h"
 #include "gather.h"
 #include "gemm_nt.h"
-#include "gemm_stream.h"
 #include "scatter.h"
 #include "select.h"
 #include "union_path.h"
@@ -429,18 +428,6 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
   MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(kGemmThreads), kGemmLdsBytes, st, prob, grid);
 }
 
-template <class P>
-void launch_gemm_stream(const char* name, const P& prob, int grid, hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<P>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
-    configured = true;
-  }
-  const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
-  MEFT_LAUNCH(name, (gemm_stream_kernel<P>), dim3(launch), dim3(kGemmThreads), kGemmLdsBytes, st, prob, grid);
-}
-
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
 void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, hipStream_t st) {
   const int n_ent = s.T * s.top_e;
@@ -530,7 +517,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokNC pv{};
     pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
     pv.d = s.d; pv.part = w.part;
-    launch_gemm_stream("value_gemm", pv, tile_bound(s, (s.d + kTN - 1) / kTN), st);
+    launch_gemm_mfma("value_gemm", pv, tile_bound(s, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(s, w.part, w, out, st);
   } else if (s.dtype == MEFT_BF16) {
     launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
@@ -574,7 +561,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
     // gathers the same dOut rows as the activation-gradient GEMM that follows it
     pn.A = w.Ap; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
-    launch_gemm_stream("dV_gemm", pn, neu_grid, st);
+    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<kTokMasked> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
@@ -585,11 +572,11 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
       ProbTokNC ph{};
       ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
       ph.d = s.d; ph.part = w.part;
-      launch_gemm_stream("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
+      launch_gemm_mfma("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
     pn.A = w.DS; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
-    launch_gemm_stream("dK_gemm", pn, neu_grid, st);
+    launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
     return launch_status();
   }
 
@@ -679,7 +666,7 @@ meft_status meft_union_fwd(const meft_shape* shape, const void* h, const void* K
   ProbTokNC pv{};
   pv.A = w.Ap; pv.W = w.Vc; pv.group_off = w.group_off; pv.sched = sched; pv.bs = g.vbs; pv.bsp = g.vbs;
   pv.d = s.d; pv.part = w.part;
-  launch_gemm_stream("union_value_gemm", pv, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
+  launch_gemm_mfma("union_value_gemm", pv, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
   launch_reduce_parts(g.vs, w.part, w, out, st);
   return launch_status();
 }
@@ -712,7 +699,7 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
     ProbTokNC ph{};
     ph.A = w.DS; ph.W = w.Kc; ph.group_off = w.group_off; ph.sched = sched; ph.bs = g.vbs; ph.bsp = g.vbs;
     ph.d = s.d; ph.part = w.part;
-    launch_gemm_stream("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
+    launch_gemm_mfma("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(g.vs, w.part, w, dh, st);
   }
   const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
@@ -721,9 +708,9 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag; pn.zrow = w.zrow;
   pn.sched = sched; pn.bs = g.vbs; pn.bsp = g.vbs; pn.d = s.d;
   pn.A = w.Ap; pn.X = gg; pn.G = w.dVc;
-  launch_gemm_stream("union_dV_gemm", pn, neu_grid, st);
+  launch_gemm_mfma("union_dV_gemm", pn, neu_grid, st);
   pn.A = w.DS; pn.X = hh; pn.G = w.dKc;
-  launch_gemm_stream("union_dK_gemm", pn, neu_grid, st);
+  launch_gemm_mfma("union_dK_gemm", pn, neu_grid, st);
   const int rows_grid = g.cap < 4096 ? g.cap : 4096;
   MEFT_LAUNCH("scatter_rows", scatter_rows_kernel, dim3(rows_grid), dim3(256), 0, st, w.dVc, S, n_S, s.N, s.d, g.cap,
               static_cast<uint16_t*>(dV));
