@@ -532,9 +532,9 @@ struct TokenSched {
 
 constexpr int kSchedSortMax = 1024;   // up to this many groups are dealt out longest first; more: round-robin
 
-// One workgroup of 1024 threads.
-__global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups,
-                                                           int cap, int2* __restrict__ grp, int* __restrict__ len) {
+// Executed by one whole workgroup of 1024 threads.
+__device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ group_off, int n_groups, int cap,
+                                                 int2* __restrict__ grp, int* __restrict__ len) {
   __shared__ int s_rows[kSchedSortMax];
   __shared__ int s_order[kSchedSortMax];
   __shared__ int s_sorted[kSchedSortMax];
@@ -588,6 +588,11 @@ __global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __rest
     grp[(size_t)x * cap + n] = make_int2(-1, tiles);
     len[x] = n;
   }
+}
+
+__global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups,
+                                                           int cap, int2* __restrict__ grp, int* __restrict__ len) {
+  build_sched_body(group_off, n_groups, cap, grp, len);
 }
 
 __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,

@@ -13,6 +13,7 @@
 #include "adam.h"
 #include "common.h"
 #include "dense_path.h"
+#include "dispatch.h"
 #include "gather.h"
 #include "gemm_nt.h"
 #include "scatter.h"
@@ -124,8 +125,15 @@ struct RouteWs {
   }
 };
 
+// the three-pass dispatch (dispatch.h) covers up to 1024 blocks and 2^20 entries
+bool fast_dispatch(const meft_shape& s) {
+  const int64_t n_ent = (int64_t)s.T * s.top_e;
+  return s.n_blocks <= kDispMaxBlocks && (n_ent + 1023) / 1024 <= kDispMaxChunks;
+}
+
 // index structures of the (token, block) dispatch, common to forward and backward
 struct DispatchWs {
+  int32_t* chunk_hist = nullptr;   // three-pass dispatch: [chunks][n_blocks]
   int32_t *sblk = nullptr, *cnt = nullptr, *group_off = nullptr, *tile_off = nullptr, *perm = nullptr,
           *tok_of_slot = nullptr, *slot_of_ent = nullptr, *sched_len = nullptr;
   int2* sched_pairs = nullptr;
@@ -140,6 +148,7 @@ struct DispatchWs {
     slot_of_ent = c.take<int32_t>(n_ent);
     sched_len = c.take<int32_t>(kXcd);
     sched_pairs = c.take<int2>((size_t)kXcd * sched_cap(s));
+    chunk_hist = c.take<int32_t>(fast_dispatch(s) ? ((n_ent + 1023) / 1024) * (size_t)s.n_blocks : 0);
   }
 };
 
@@ -431,6 +440,19 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
 void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, hipStream_t st) {
   const int n_ent = s.T * s.top_e;
+  if (fast_dispatch(s)) {
+    const int n_chunks = (n_ent + 1023) / 1024;
+    const size_t lds = (size_t)16 * s.n_blocks * sizeof(int);
+    MEFT_LAUNCH("dispatch_count", dispatch_count_kernel, dim3(n_chunks), dim3(1024), lds, st, w.sblk, n_ent,
+                s.n_blocks, w.chunk_hist);
+    MEFT_LAUNCH("dispatch_scan", dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, w.chunk_hist, n_chunks,
+                s.n_blocks, BM, w.cnt, w.group_off, w.tile_off, sched_cap(s), dense ? w.sched_pairs : nullptr,
+                w.sched_len);
+    MEFT_LAUNCH("dispatch_place", dispatch_place_kernel, dim3(n_chunks), dim3(1024), lds, st, w.sblk, n_ent,
+                s.n_blocks, s.top_e, w.chunk_hist, w.group_off, w.perm, dense ? w.tok_of_slot : nullptr,
+                w.slot_of_ent, kSlotPad);
+    return;
+  }
   MEFT_LAUNCH("count_blocks", count_blocks_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, n_ent, w.cnt);
   MEFT_LAUNCH("fill_groups", fill_groups_kernel, dim3(s.n_blocks), dim3(1024), 0, st, w.sblk, n_ent, w.cnt,
               s.n_blocks, BM, w.group_off, w.tile_off, w.perm);
