@@ -265,25 +265,37 @@ __global__ __launch_bounds__(256) void slot_maps_kernel(const int32_t* __restric
   }
 }
 
-// Backward: scatter the saved activations into A' (slot-major) and mark touched neurons.  A' and the flags must
-// be zero before.  One thread per (token, neuron) pair.
-__global__ void scatter_act_kernel(const int32_t* __restrict__ idx, const float* __restrict__ act, int P, int k,
-                                   int N, int bs, int bsp, int e, const int32_t* __restrict__ sblk,
-                                   const int32_t* __restrict__ slot_of_ent, uint16_t* __restrict__ Ap,
-                                   int32_t* __restrict__ flag) {
-  const int p = blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= P) return;
-  const int t = p / k;
-  const int j = clampi(idx[p], 0, N - 1);
-  const int b = j / bs, r = j - b * bs;
-  flag[j] = 1;
-  int q = -1;
-  for (int z = 0; z < e; ++z)
-    if (sblk[(size_t)t * e + z] == b) { q = z; break; }
-  if (q < 0) return;
-  const int slot = slot_of_ent[t * e + q];
-  const uint16_t v = (uint16_t)f32_to_bf16_bits(act[p]);
-  Ap[(size_t)slot * bsp + r] = v;
+// Backward: the token's dense activation rows A'[slot, 0:bsp] (one per block it uses, slot-major, bf16(act) where
+// a neuron was selected, else 0) from the saved (idx, act), and the touched flags (zero before).  One workgroup
+// per token: the rows are put together in LDS and written whole, 16 bytes per thread and step.
+// Dynamic LDS: e * bsp * 2 bytes.
+__global__ __launch_bounds__(256) void act_rows_kernel(const int32_t* __restrict__ idx, const float* __restrict__ act,
+                                                       int k, int N, int bs, int bsp, int e,
+                                                       const int32_t* __restrict__ sblk,
+                                                       const int32_t* __restrict__ slot_of_ent,
+                                                       uint16_t* __restrict__ Ap, int32_t* __restrict__ flag) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t s_rows[];   // [e][bsp]
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const int words = e * bsp / 8;   // 16-byte words
+  u32x4* s4 = reinterpret_cast<u32x4*>(s_rows);
+  for (int w = tid; w < words; w += 256) s4[w] = u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();
+  for (int p = tid; p < k; p += 256) {
+    const int j = clampi(idx[(size_t)t * k + p], 0, N - 1);
+    const int b = j / bs, r = j - b * bs;
+    flag[j] = 1;
+    int q = -1;
+    for (int z = 0; z < e; ++z)
+      if (sblk[(size_t)t * e + z] == b) { q = z; break; }
+    if (q >= 0) s_rows[q * bsp + r] = (uint16_t)f32_to_bf16_bits(act[(size_t)t * k + p]);
+  }
+  __syncthreads();
+  const int wpr = bsp / 8;   // words per row
+  for (int w = tid; w < words; w += 256) {
+    const int q = w / wpr, c = w - q * wpr;
+    if (sblk[(size_t)t * e + q] < 0) continue;   // fewer than e blocks in use: no slot
+    reinterpret_cast<u32x4*>(Ap + (size_t)slot_of_ent[t * e + q] * bsp)[c] = s4[w];
+  }
 }
 
 // out[t, :] = sum over the token's entries of part[slot(entry), :] (bf16 partials, fp32 sum), rounded to bf16.

@@ -107,8 +107,6 @@ struct TileCoord {
 //                the policy wants next to the two values of (m, n), e.g. a mask; called for every position of the
 //                tile, stored or not, so the policy clamps m and n to valid ones
 
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
 // Eight transposing LDS reads (the four n-contiguous B fragments of one k16 step, low and high k half)
 // followed by the wait for them.  Written as one asm block: issued through the builtin, the compiler
 // would order these reads after every outstanding global->LDS load (it cannot tell the stages apart),

@@ -188,7 +188,7 @@ struct BwdWs : DispatchWs {
       carve(s, c);
       const size_t n_ent = (size_t)s.T * s.top_e;
       chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
-      flag = c.take<int32_t>(s.N);                               // flag, zrow and Ap adjacent: cleared by one fill
+      flag = c.take<int32_t>(s.N);                               // flag and zrow adjacent: cleared by one fill
       zrow = c.take<uint16_t>(round64(s.block_size));
       Ap = c.take<uint16_t>(n_ent * round64(s.block_size));
       DS = c.take<uint16_t>(n_ent * round64(s.block_size));
@@ -563,11 +563,11 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
                 st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
     launch_dispatch(s, w, kGemmBM, true, st);
-    // flag, the row of zeros and A' start from zero (adjacent in the workspace); 4-byte fill
-    const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.DS) - reinterpret_cast<char*>(w.flag)) / 4;
+    // the flags and the row of zeros start from zero (adjacent in the workspace); 4-byte fill
+    const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.Ap) - reinterpret_cast<char*>(w.flag)) / 4;
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
                 clear_words, 0);
-    MEFT_LAUNCH("scatter_act", scatter_act_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, act, P, s.top_k,
+    MEFT_LAUNCH("act_rows", act_rows_kernel, dim3(s.T), dim3(256), (size_t)s.top_e * bsp * 2, st, idx, act, s.top_k,
                 s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.Ap, w.flag);
     const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
     MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
