@@ -36,3 +36,13 @@ def test_largest_number_of_blocks(P):
 def test_largest_candidate_set(P):
     # two tokens over one block of 4194304 neurons
     _case(P, T=2, d=8, n_blocks=1, block_size=4194304, top_e=1, top_k=100, dtype="f32", seed=1004)
+
+
+def test_dispatch_at_the_three_pass_limit_of_blocks(P):
+    # 1024 blocks: the per-wave block counters of the three-pass dispatch fill 64 KB of LDS; several chunks of entries
+    _case(P, T=700, d=64, n_blocks=1024, block_size=16, top_e=3, top_k=8, dtype="bf16", seed=1005)
+
+
+def test_matrix_core_path_beyond_the_three_pass_dispatch(P):
+    # more than 1024 blocks: the per-block dispatch kernels and the round-robin tile schedule, on the matrix-core path
+    _case(P, T=300, d=64, n_blocks=1100, block_size=16, top_e=3, top_k=8, dtype="bf16", seed=1006)
