@@ -9,8 +9,8 @@
 //     dOut, h are contiguous in d: the value sum of Eq. 4, dh, dK, dV;
 //   A m-contiguous (rows indexed by k): dK, dV, whose A operand is the slot-major activation matrix, read as it is.
 //
-// Tile 128 (m) x 256 (n) x 64 (k); 4 compute waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles, plus two
-// loader waves that own the whole global -> LDS traffic (global_load_lds, 16 B per lane).  Three stages of 48 KB
+// Tile 128 (m) x 256 (n) x 64 (k); 4 compute waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles, plus two or
+// four loader waves that own the whole global -> LDS traffic (global_load_lds, 16 B per lane).  Three stages of 48 KB
 // form a ring.  LDS layouts are XOR-swizzled so that both the linear DMA writes and the fragment reads are free of
 // bank conflicts:
 //   k-contiguous operand: rows of 64 k = 8 chunks of 16 B; logical chunk c of row r sits at chunk
@@ -23,7 +23,7 @@
 // The k tiles of all the tiles a workgroup works through form ONE stream through the ring: the loaders request
 // stream position s + 2 right after the barrier that hands position s to the compute waves, whether or not s + 2
 // belongs to the next output tile, so the operand pipeline never drains at a tile boundary.  There is exactly one
-// workgroup barrier per k tile of the stream, executed by all six waves.  (An extra barrier at the end of every
+// workgroup barrier per k tile of the stream, executed by all the waves.  (An extra barrier at the end of every
 // tile, releasing its last stage before the stores so that the loaders request a third k tile during the epilogue,
 // was measured and did not pay.)
 //
@@ -48,10 +48,12 @@ constexpr int kTM = 128, kTN = 256, kTK = 64, kStages = 3;
 constexpr int kStageElems = (kTM + kTN) * kTK;                 // 24576 bf16 = 48 KB
 constexpr int kOperandLdsBytes = kStages * kStageElems * 2;    // 144 KB
 constexpr int kIdRingSlots = 4;                                // k tiles of gathered-row numbers kept per loader
-constexpr int kGemmLdsBytes = kOperandLdsBytes + 2 * kIdRingSlots * 64 * 4;   // + 2 KB
+constexpr int kMaxLoaders = 4;
+constexpr int kGemmLdsBytes = kOperandLdsBytes + kMaxLoaders * kIdRingSlots * 64 * 4;   // + 1 KB per loader
 constexpr int kXcd = 8;
-constexpr int kLoaders = 2;    // waves that only request operands (the other four only compute)
-constexpr int kGemmThreads = 256 + 64 * kLoaders;
+// threads of a launch: four compute waves plus the policy's loader waves
+template <class P>
+constexpr int gemm_threads() { return 256 + 64 * P::kLoaders; }
 
 #define MEFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define MEFT_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -75,6 +77,7 @@ struct TileCoord {
 };
 
 // A problem policy P provides:
+//   static constexpr int kLoaders;                      loader waves, 2 or 4
 //   __device__ bool locate(int wg, TileCoord&) const;   false: no tile with id wg, nor with any larger id on
 //                                                       the same XCD (ids wg + 8, wg + 16, ...)
 //   static constexpr bool kAMC;                         A contiguous along m (rows indexed by k)?
@@ -160,13 +163,16 @@ __device__ __forceinline__ void tr_read12(u32x2 (&oa)[4], u32x2 (&ob)[8], const 
 // operand loads that have to have landed instead.)
 #define MEFT_BARRIER_LDS() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
-// Four compute waves (tid 0..255) and kLoaders loader waves.  The loaders own the whole global -> LDS traffic:
+// Four compute waves (tid 0..255) and P::kLoaders loader waves (two, or four where the loaders' own instruction
+// stream paces the loads: row numbers to look up, an address to form per load).  The loaders own the whole global -> LDS traffic:
 // measured on gfx950 the operand path, not the matrix cores or LDS, bounds these contractions (a compute unit keeps
 // about a hundred 128-byte read requests in flight, no more), and a wave that both requests operands and issues
 // MFMAs keeps neither queue full.  The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ...
 // (gridDim.x is a multiple of 8, so it stays on one XCD's list).
 template <class P>
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
+__global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
+  constexpr int kLoaders = P::kLoaders;
+  static_assert(kLoaders == 2 || kLoaders == 4, "loader waves: 2 or 4");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -180,8 +186,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
   if (wave >= 4) {
     // ------------------------------------------------------------------ loader waves
     const int lw = wave - 4;
-    constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (1 KB each) per loader and stage: 8
-    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (1 KB each) per loader and stage: 16
+    constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (1 KB each) per loader and stage: 8 or 4
+    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (1 KB each) per loader and stage: 16 or 8
     static_assert(LA + LB <= 63, "partial vmcnt wait out of range");
     const int lr8 = lane >> 3;
     int* idring = reinterpret_cast<int*>(smem + kOperandLdsBytes / 2) + lw * kIdRingSlots * 64;
@@ -261,7 +267,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
         // outstanding operand load)
         const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(
             idring + (n_o & (kIdRingSlots - 1)) * 64 + 2 * lw * LB + half);
-        static_assert(LB == 16, "the block below reads sixteen row numbers");
+        if constexpr (LB == 16) {
         asm volatile(
             "ds_read_b32 %0, %16\n\tds_read_b32 %1, %16 offset:8\n\tds_read_b32 %2, %16 offset:16\n\t"
             "ds_read_b32 %3, %16 offset:24\n\tds_read_b32 %4, %16 offset:32\n\tds_read_b32 %5, %16 offset:40\n\t"
@@ -274,6 +280,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_mfma_kernel(P p, int n_t
               "=&v"(ids[13]), "=&v"(ids[14]), "=&v"(ids[15])
             : "v"(a)
             : "memory");
+        } else {
+        static_assert(LB == 16 || LB == 8, "row-number reads are written out for 16 and 8 loads");
+        asm volatile(
+            "ds_read_b32 %0, %8\n\tds_read_b32 %1, %8 offset:8\n\tds_read_b32 %2, %8 offset:16\n\t"
+            "ds_read_b32 %3, %8 offset:24\n\tds_read_b32 %4, %8 offset:32\n\tds_read_b32 %5, %8 offset:40\n\t"
+            "ds_read_b32 %6, %8 offset:48\n\tds_read_b32 %7, %8 offset:56\n\ts_waitcnt lgkmcnt(0)"
+            : "=&v"(ids[0]), "=&v"(ids[1]), "=&v"(ids[2]), "=&v"(ids[3]), "=&v"(ids[4]), "=&v"(ids[5]), "=&v"(ids[6]),
+              "=&v"(ids[7])
+            : "v"(a)
+            : "memory");
+        }
       } else if constexpr (P::kBNC) {
 #pragma unroll
         for (int i = 0; i < LB; ++i) ids[i] = p.b_row_ids(t_o, k_o * kTK + 2 * (lw * LB + i) + half);

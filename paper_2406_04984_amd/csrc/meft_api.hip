@@ -434,7 +434,7 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
   // persistent workgroups: one per compute unit (the LDS footprint allows no more), each walking the tile ids
   // wg, wg + 256, ... below `grid`
   const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
-  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(kGemmThreads), kGemmLdsBytes, st, prob, grid);
+  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(gemm_threads<P>()), kGemmLdsBytes, st, prob, grid);
 }
 
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
