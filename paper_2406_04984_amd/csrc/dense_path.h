@@ -173,14 +173,15 @@ struct ProbTokNC {
 //   G_b[bs, d] = sum over the slots of group b of A[slot, 0:bs]^T . X[token(slot), :]
 // (A = A', X = dOut: dV;  A = DS', X = h: dK).  A is the slot-major matrix the token-major kernels write and read,
 // so no transposed copy of the activations exists.  The contraction length is padded to 64: the padding rows of A
-// come from a row of zeros, those of X are any valid rows.  Only rows whose neuron is touched are written.
+// come from a row of zeros that the workspace keeps in front of the activation matrices, those of X are any valid
+// rows.  Only rows whose neuron is touched are written.
 struct ProbNeuTN {
   static constexpr int kLoaders = 4;   // measured: 0.425 -> 0.388 ms (dV) against two
   static constexpr bool kAMC = true;
   static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = true;
   const uint16_t* A;          // [slots, bsp]
-  const uint16_t* zrow;       // bsp zeros
+  int zrow;                   // number of a row of bsp zeros, counted from A's row 0 (it lies before A: negative)
   const uint16_t* X;          // [T, d]
   const int32_t* group_off; const int32_t* tok_of_slot;
   const int32_t* flag;        // [N] > 0 where some token selected the neuron
@@ -200,10 +201,9 @@ struct ProbNeuTN {
     tc.aux = rows;
     return true;
   }
+  __device__ const uint16_t* a_mat() const { return A; }
   __device__ int a_cols(const TileCoord&) const { return bsp; }
-  __device__ const uint16_t* a_krow(const TileCoord& tc, int k) const {
-    return k < tc.aux ? A + (size_t)(tc.slot0 + k) * bsp : zrow;
-  }
+  __device__ int a_krow(const TileCoord& tc, int k) const { return k < tc.aux ? tc.slot0 + k : zrow; }
   // tok_of_slot is padded by kSlotPad valid entries, which covers the padded contraction length
   __device__ const int32_t* b_row_id_src(const TileCoord& tc, int k0) const { return tok_of_slot + tc.slot0 + k0; }
   __device__ const uint16_t* b_row_ptr(int row) const { return X + (size_t)row * d; }

@@ -82,9 +82,10 @@ struct TileCoord {
 //                                                       the same XCD (ids wg + 8, wg + 16, ...)
 //   static constexpr bool kAMC;                         A contiguous along m (rows indexed by k)?
 //       false: __device__ const uint16_t* a_row(const TileCoord&, int m) const;    start of row m (clamped)
-//       true:  __device__ const uint16_t* a_krow(const TileCoord&, int k) const;   start of the row that holds
-//              contraction index k (a row of zeros beyond the contraction length), and
-//              __device__ int a_cols(const TileCoord&) const;                      its length (a multiple of 8)
+//       true:  __device__ const uint16_t* a_mat() const;                 row 0 of the matrix that holds A,
+//              __device__ int a_cols(const TileCoord&) const;            its row length (a multiple of 8), and
+//              __device__ int a_krow(const TileCoord&, int k) const;     the number of the row that holds contraction
+//              index k (possibly negative; a row of zeros beyond the contraction length)
 //   static constexpr bool kBNC;                         B contiguous along n (rows indexed by k)?
 //       false: __device__ const uint16_t* b_row(const TileCoord&, int n) const;    start of B row n (clamped)
 //       true:  __device__ const uint16_t* b_row_ptr(int row) const;   start of B row `row`; rows are
@@ -213,20 +214,26 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     // B, n-contiguous: a wave-load covers two k rows (lanes 0..31 the even one, lanes 32..63 the odd one), 512 bytes
     //   of each; lane l fetches the chunk (l & 31) ^ (2 * (row & 7)); row & 7 only depends on i & 3, so four
     //   column offsets per tile cover all the loads.
-    const uint16_t* pa[P::kAMC ? 1 : LA];
-    int acol = 0;
+    //
+    // Every wave-load fills 1 KB of LDS, and the loads of a loader fill consecutive kilobytes.  The instruction's
+    // immediate offset is added to the global AND the LDS address (checked on the device), so four consecutive loads
+    // share one LDS base (one write of M0 instead of four) with offsets 0, 1, 2, 3 KB, and the global pointers are
+    // set up that many bytes lower.
+    const uint16_t* pa[P::kAMC ? 4 : LA];   // m-contiguous: row 0 at this lane's column, one per offset 0..3 KB
     const uint16_t* pb[P::kBNC ? 4 : LB];
     const int half = lane >> 5;
     auto setup = [&]() {
       if constexpr (P::kAMC) {
         const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
         const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
-        acol = col > last ? last : col;                                 // clamp (rows beyond Mrows are never stored)
+        const int acol = col > last ? last : col;                       // clamp (rows beyond Mrows are never stored)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) pa[q] = p.a_mat() + (acol - q * 512);
       } else {
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
           const int row = (lw * LA + i) * 8 + lr8;
-          pa[i] = p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+          pa[i] = p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
         }
       }
       if constexpr (P::kBNC) {
@@ -235,16 +242,29 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
           const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
           int col = t_o.n0 + chunk * 8;
           col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;              // clamp (columns beyond Ncols are never stored)
-          pb[q] = p.b_row_ptr(0) + col;
+          pb[q] = p.b_row_ptr(0) + col - q * 512;
         }
       } else {
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
           const int row = (lw * LB + i) * 8 + lr8;
-          pb[i] = p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+          pb[i] = p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
         }
       }
     };
+    // load number i of a loader into the 1 KB slot i of its part of an operand region (see above)
+    // (the offset has to be a literal: the switch folds away once the loop over i is unrolled)
+#define MEFT_LOAD_1K(src, region, i)                                                    \
+  do {                                                                                  \
+    const auto* g_ = MEFT_GPTR(src);                                                    \
+    auto* l_ = MEFT_LPTR((region) + ((i) & ~3) * 512);                                  \
+    switch ((i) & 3) {                                                                  \
+      case 0: __builtin_amdgcn_global_load_lds(g_, l_, 16, 0, 0); break;                \
+      case 1: __builtin_amdgcn_global_load_lds(g_, l_, 16, 1024, 0); break;             \
+      case 2: __builtin_amdgcn_global_load_lds(g_, l_, 16, 2048, 0); break;             \
+      default: __builtin_amdgcn_global_load_lds(g_, l_, 16, 3072, 0); break;            \
+    }                                                                                   \
+  } while (0)
 
     auto request_ids = [&]() {
       if constexpr (P::kBNC && P::kRowIdsInMemory) {
@@ -295,13 +315,18 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
         for (int i = 0; i < LB; ++i) ids[i] = p.b_row_ids(t_o, k_o * kTK + 2 * (lw * LB + i) + half);
       }
+      [[maybe_unused]] int a_row_bytes = 0;
+      if constexpr (P::kAMC) a_row_bytes = p.a_cols(t_o) * 2;
+      uint16_t* my_a = sa + lw * LA * 512;   // 512 elements = 1 KB per load
+      uint16_t* my_b = sb + lw * LB * 512;
 #pragma unroll
       for (int i = 0; i < LA; ++i) {
         if constexpr (P::kAMC) {
-          const uint16_t* src = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4)) + acol;
-          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sa + (lw * LA + i) * 4 * kTM), 16, 0, 0);
+          const int row = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4));
+          const char* src = reinterpret_cast<const char*>(pa[i & 3]) + (int64_t)row * a_row_bytes;
+          MEFT_LOAD_1K(src, my_a, i);
         } else {
-          __builtin_amdgcn_global_load_lds(MEFT_GPTR(pa[i] + k_o * kTK), MEFT_LPTR(sa + (lw * LA + i) * 8 * kTK), 16, 0, 0);
+          MEFT_LOAD_1K(pa[i] + k_o * kTK, my_a, i);
         }
       }
       if constexpr (P::kBNC) {
@@ -309,12 +334,11 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
           const char* src = reinterpret_cast<const char*>(pb[i & 3]) + (uint64_t)(uint32_t)ids[i] * row_bytes;
-          __builtin_amdgcn_global_load_lds(MEFT_GPTR(src), MEFT_LPTR(sb + (lw * LB + i) * 512), 16, 0, 0);
+          MEFT_LOAD_1K(src, my_b, i);
         }
       } else {
 #pragma unroll
-        for (int i = 0; i < LB; ++i)
-          __builtin_amdgcn_global_load_lds(MEFT_GPTR(pb[i] + k_o * kTK), MEFT_LPTR(sb + (lw * LB + i) * 8 * kTK), 16, 0, 0);
+        for (int i = 0; i < LB; ++i) MEFT_LOAD_1K(pb[i] + k_o * kTK, my_b, i);
       }
       ++n_o;
       stage_o = stage_o + 1 == kStages ? 0 : stage_o + 1;

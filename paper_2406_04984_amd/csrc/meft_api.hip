@@ -189,9 +189,12 @@ struct BwdWs : DispatchWs {
       const size_t n_ent = (size_t)s.T * s.top_e;
       chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
       flag = c.take<int32_t>(s.N);                               // flag and zrow adjacent: cleared by one fill
-      zrow = c.take<uint16_t>(round64(s.block_size));
-      Ap = c.take<uint16_t>(n_ent * round64(s.block_size));
-      DS = c.take<uint16_t>(n_ent * round64(s.block_size));
+      // one piece: the row of zeros, A', DS', each row bsp elements, so that the zero row is row -1 of A' and row
+      // -(n_ent + 1) of DS'
+      const size_t bsp = round64(s.block_size);
+      zrow = c.take<uint16_t>(bsp * (1 + 2 * n_ent));
+      Ap = zrow ? zrow + bsp : nullptr;
+      DS = zrow ? Ap + n_ent * bsp : nullptr;
       part = c.take<uint16_t>(n_ent * s.d);
     } else {
       ds = c.take<float>(P);
@@ -339,9 +342,9 @@ struct UnionWs : DispatchWs {
     Vc = c.take<uint16_t>(rows * s.d);
     dKc = c.take<uint16_t>(rows * s.d);
     dVc = c.take<uint16_t>(rows * s.d);
-    zrow = c.take<uint16_t>(g.vbs);
-    Ap = c.take<uint16_t>(n_ent * g.vbs);
-    DS = c.take<uint16_t>(n_ent * g.vbs);
+    zrow = c.take<uint16_t>((size_t)g.vbs * (1 + 2 * n_ent));   // one piece: row of zeros, A', DS' (see BwdWs)
+    Ap = zrow ? zrow + g.vbs : nullptr;
+    DS = zrow ? Ap + n_ent * g.vbs : nullptr;
     part = c.take<uint16_t>(n_ent * s.d);
     bytes = c.off < 256 ? 256 : c.off;
   }
@@ -578,11 +581,12 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
     const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
     ProbNeuTN pn{};
-    pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag; pn.zrow = w.zrow;
+    pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
     pn.sched = sched; pn.bs = s.block_size; pn.bsp = bsp; pn.d = s.d;
+    const int n_ent = s.T * s.top_e;
     // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
     // gathers the same dOut rows as the activation-gradient GEMM that follows it
-    pn.A = w.Ap; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
+    pn.A = w.Ap; pn.zrow = -1; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
     launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<kTokMasked> pg{};
@@ -597,7 +601,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
       launch_gemm_mfma("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
-    pn.A = w.DS; pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
+    pn.A = w.DS; pn.zrow = -(n_ent + 1); pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
     launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
     return launch_status();
   }
@@ -727,11 +731,11 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
   const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
   ProbNeuTN pn{};
-  pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag; pn.zrow = w.zrow;
+  pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;
   pn.sched = sched; pn.bs = g.vbs; pn.bsp = g.vbs; pn.d = s.d;
-  pn.A = w.Ap; pn.X = gg; pn.G = w.dVc;
+  pn.A = w.Ap; pn.zrow = -1; pn.X = gg; pn.G = w.dVc;
   launch_gemm_mfma("union_dV_gemm", pn, neu_grid, st);
-  pn.A = w.DS; pn.X = hh; pn.G = w.dKc;
+  pn.A = w.DS; pn.zrow = -(s.T * g.nvb + 1); pn.X = hh; pn.G = w.dKc;
   launch_gemm_mfma("union_dK_gemm", pn, neu_grid, st);
   const int rows_grid = g.cap < 4096 ? g.cap : 4096;
   MEFT_LAUNCH("scatter_rows", scatter_rows_kernel, dim3(rows_grid), dim3(256), 0, st, w.dVc, S, n_S, s.N, s.d, g.cap,
