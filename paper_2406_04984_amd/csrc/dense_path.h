@@ -52,6 +52,7 @@ struct ProbRouter {
   }
   __device__ int out_cols(const TileCoord&) const { return B; }
   static constexpr bool kAux = false;
+  static constexpr bool kOutBf16 = false;
   __device__ int row_tag(const TileCoord&, int m) const { return m < T ? 1 : 0; }
   __device__ size_t row_off(const TileCoord& tc, int, int m) const { return ((size_t)tc.aux * T + m) * B; }
   __device__ void store2(size_t at, int n, float v0, float v1, uint32_t) const {
@@ -110,29 +111,29 @@ struct ProbTokKC {
     const int mm = m < tc.Mrows ? m : tc.Mrows - 1, nn = n < bsp ? n : bsp - 2;
     return *reinterpret_cast<const uint32_t*>(Ap + (size_t)(tc.slot0 + mm) * bsp + nn);
   }
-  __device__ void store2(size_t at, int n, float v0, float v1, uint32_t mk) const {
-    if constexpr (MODE == kTokScores) {
-      if ((bs & 1) == 0) {   // rows are 8-byte aligned and n + 1 < bs whenever n < bs
-        if (n < bs) *reinterpret_cast<f32x2_hw*>(sc + at) = f32x2_hw{v0, v1};
-      } else {
-        if (n < bs) sc[at] = v0;
-        if (n + 1 < bs) sc[at + 1] = v1;
-      }
+  static constexpr bool kOutBf16 = MODE != kTokScores;
+  __device__ void store2(size_t at, int n, float v0, float v1, uint32_t) const {   // kTokScores
+    if ((bs & 1) == 0) {   // rows are 8-byte aligned and n + 1 < bs whenever n < bs
+      if (n < bs) *reinterpret_cast<f32x2_hw*>(sc + at) = f32x2_hw{v0, v1};
     } else {
-      if (n >= bsp) return;   // bsp is even: n + 1 < bsp
-      if constexpr (MODE == kTokMasked) {
-        // keep the gradient where the activation is positive (A' holds zeros in the columns bs..bsp)
-        const bool on0 = (mk & 0x7FFFu) != 0u && (mk & 0x8000u) == 0u;
-        const bool on1 = (mk & 0x7FFF0000u) != 0u && (mk & 0x80000000u) == 0u;
-        v0 = on0 ? v0 : 0.f;
-        v1 = on1 ? v1 : 0.f;
-      } else {
-        // columns beyond the block (computed from clamped operand rows) are zero
-        v0 = (n < bs && v0 > 0.f) ? v0 : 0.f;
-        v1 = (n + 1 < bs && v1 > 0.f) ? v1 : 0.f;
-      }
-      *reinterpret_cast<uint32_t*>(DS + at) = pack_bf16x2(v0, v1);
+      if (n < bs) sc[at] = v0;
+      if (n + 1 < bs) sc[at + 1] = v1;
     }
+  }
+  __device__ void store_pk(size_t at, int n, uint32_t pk, uint32_t mk) const {   // kTokMasked, kTokRelu
+    if (n >= bsp) return;   // bsp is even: n + 1 < bsp
+    // a half is kept where the deciding value is positive: sign bit clear and not zero
+    uint32_t keep = 0u;
+    if constexpr (MODE == kTokMasked) {
+      // decided by the activations (A' holds zeros in the columns bs..bsp)
+      if ((mk & 0x7FFFu) != 0u && (mk & 0x8000u) == 0u) keep |= 0xFFFFu;
+      if ((mk & 0x7FFF0000u) != 0u && (mk & 0x80000000u) == 0u) keep |= 0xFFFF0000u;
+    } else {
+      // ReLU of the value itself; columns beyond the block (computed from clamped operand rows) are zero
+      if (n < bs && (pk & 0x7FFFu) != 0u && (pk & 0x8000u) == 0u) keep |= 0xFFFFu;
+      if (n + 1 < bs && (pk & 0x7FFF0000u) != 0u && (pk & 0x80000000u) == 0u) keep |= 0xFFFF0000u;
+    }
+    *reinterpret_cast<uint32_t*>(DS + at) = pk & keep;
   }
 };
 
@@ -164,9 +165,8 @@ struct ProbTokNC {
   static constexpr bool kAux = false;
   __device__ int row_tag(const TileCoord& tc, int m) const { return m < tc.Mrows ? 1 : 0; }
   __device__ size_t row_off(const TileCoord& tc, int, int m) const { return (size_t)(tc.slot0 + m) * d; }
-  __device__ void store2(size_t at, int, float v0, float v1, uint32_t) const {
-    *reinterpret_cast<uint32_t*>(part + at) = pack_bf16x2(v0, v1);
-  }
+  static constexpr bool kOutBf16 = true;
+  __device__ void store_pk(size_t at, int, uint32_t pk, uint32_t) const { *reinterpret_cast<uint32_t*>(part + at) = pk; }
 };
 
 // Neuron-major, both operands indexed by the contraction index (slot) in their rows:
@@ -213,9 +213,8 @@ struct ProbNeuTN {
   }
   static constexpr bool kAux = false;
   __device__ size_t row_off(const TileCoord& tc, int, int m) const { return ((size_t)tc.g * bs + m) * d; }
-  __device__ void store2(size_t at, int, float v0, float v1, uint32_t) const {
-    *reinterpret_cast<uint32_t*>(G + at) = pack_bf16x2(v0, v1);
-  }
+  static constexpr bool kOutBf16 = true;
+  __device__ void store_pk(size_t at, int, uint32_t pk, uint32_t) const { *reinterpret_cast<uint32_t*>(G + at) = pk; }
 };
 
 // ---- helper kernels ----------------------------------------------------------------------------

@@ -28,9 +28,9 @@
 // was measured and did not pay.)
 //
 // The epilogue needs neither LDS nor barriers: neighbouring lanes exchange one accumulator value through a DPP
-// move, so that every lane holds two adjacent columns of one row, and hands them to the policy, which converts and
-// stores them (4 bytes of bf16 or 8 bytes of fp32 per lane; a half wave writes 64 or 128 contiguous bytes of each
-// of two rows per instruction).  While the compute waves store, the loaders are already two k tiles into the next
+// move, so that every lane holds two adjacent columns of one row, and hands them to the policy, which stores them
+// (4 bytes of bf16, converted before the exchange, or 8 bytes of fp32 per lane; a half wave writes 64 or 128
+// contiguous bytes of each of two rows per instruction).  While the compute waves store, the loaders are already two k tiles into the next
 // tile.
 //
 // Workgroups are mapped to tiles XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs,
@@ -104,9 +104,12 @@ struct TileCoord {
 //                before the k loop.
 //   __device__ size_t row_off(const TileCoord&, int tag, int m) const;   element offset of (row m, column 0) in
 //                the output array
-//   __device__ void store2(size_t at, int n, float v0, float v1, uint32_t aux) const;   store C[m][n] = v0 and
-//                C[m][n + 1] = v1 at element offset `at` (= row_off + n; n even, n < round-up of out_cols to 32; the
-//                policy checks n and n + 1 against out_cols where that is not a multiple of 32)
+//   static constexpr bool kOutBf16;   the output is bf16 (the kernel converts, two columns to a word) or fp32
+//       false: __device__ void store2(size_t at, int n, float v0, float v1, uint32_t aux) const;   store C[m][n] = v0
+//                and C[m][n + 1] = v1 at element offset `at` (= row_off + n; n even, n < round-up of out_cols to 32;
+//                the policy checks n and n + 1 against out_cols where that is not a multiple of 32)
+//       true:  __device__ void store_pk(size_t at, int n, uint32_t pk, uint32_t aux) const;   the same with
+//                pk = bf16(C[m][n]) | bf16(C[m][n + 1]) << 16
 //   static constexpr bool kAux;  true: __device__ uint32_t load_aux(const TileCoord&, int m, int n) const;   a word
 //                the policy wants next to the two values of (m, n), e.g. a mask; called for every position of the
 //                tile, stored or not, so the policy clamps m and n to valid ones
@@ -522,26 +525,53 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
         for (int q = 0; q < 8; ++q) {
           const int r = 2 * q;
           const int rl = i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3) + (lane & 1);
-          float lo[4], hi[4];
+          if constexpr (P::kOutBf16) {
+            // bf16 output: both rows' values of this lane's column are packed first, (row m | row m+1 << 16); one
+            // neighbour swap of the packed word and one byte permute give (column c | column c+1 << 16) of the
+            // lane's row (even lanes: row m from the low halves, odd lanes: row m+1 from the high halves)
+            const uint32_t sel = odd ? 0x03020706u : 0x05040100u;   // bytes 0-3: own word, 4-7: the neighbour's
+            uint32_t pk[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
-            const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
-            const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
-            lo[j] = odd ? bn : a;
-            hi[j] = odd ? b : an;
-          }
-          if (tag[q] != 0) {
-            const size_t at = p.row_off(tc, tag[q], tc.m0 + wm + rl) + ncol;
-            if (nj >= 4) {
-              p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
-              p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
-              p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
-              p.store2(at + 96, ncol + 96, lo[3], hi[3], aux[q][3]);
-            } else {
-              if (nj > 0) p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
-              if (nj > 1) p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
-              if (nj > 2) p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
+            for (int j = 0; j < 4; ++j) {
+              const uint32_t own = pack_bf16x2(acc[i][j][r], acc[i][j][r + 1]);
+              const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp((int)own, (int)own, 0xB1, 0xF, 0xF, true);
+              pk[j] = __builtin_amdgcn_perm(nb, own, sel);
+            }
+            if (tag[q] != 0) {
+              const size_t at = p.row_off(tc, tag[q], tc.m0 + wm + rl) + ncol;
+              if (nj >= 4) {
+                p.store_pk(at, ncol, pk[0], aux[q][0]);
+                p.store_pk(at + 32, ncol + 32, pk[1], aux[q][1]);
+                p.store_pk(at + 64, ncol + 64, pk[2], aux[q][2]);
+                p.store_pk(at + 96, ncol + 96, pk[3], aux[q][3]);
+              } else {
+                if (nj > 0) p.store_pk(at, ncol, pk[0], aux[q][0]);
+                if (nj > 1) p.store_pk(at + 32, ncol + 32, pk[1], aux[q][1]);
+                if (nj > 2) p.store_pk(at + 64, ncol + 64, pk[2], aux[q][2]);
+              }
+            }
+          } else {
+            float lo[4], hi[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
+              const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
+              const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
+              lo[j] = odd ? bn : a;
+              hi[j] = odd ? b : an;
+            }
+            if (tag[q] != 0) {
+              const size_t at = p.row_off(tc, tag[q], tc.m0 + wm + rl) + ncol;
+              if (nj >= 4) {
+                p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
+                p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
+                p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
+                p.store2(at + 96, ncol + 96, lo[3], hi[3], aux[q][3]);
+              } else {
+                if (nj > 0) p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
+                if (nj > 1) p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
+                if (nj > 2) p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
+              }
             }
           }
         }
