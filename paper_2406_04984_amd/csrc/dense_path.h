@@ -54,6 +54,8 @@ struct ProbRouter {
   static constexpr bool kAux = false;
   static constexpr bool kOutBf16 = false;
   __device__ int row_tag(const TileCoord&, int m) const { return m < T ? 1 : 0; }
+  static constexpr bool kRowsLinear = true;
+  __device__ int out_ld(const TileCoord&) const { return B; }
   __device__ size_t row_off(const TileCoord& tc, int, int m) const { return ((size_t)tc.aux * T + m) * B; }
   __device__ void store2(size_t at, int n, float v0, float v1, uint32_t) const {
     if (n < B) p[at] = v0;
@@ -102,6 +104,8 @@ struct ProbTokKC {
     if (m >= tc.Mrows) return 0;
     return MODE == kTokScores ? perm[tc.slot0 + m] + 1 : 1;
   }
+  static constexpr bool kRowsLinear = MODE != kTokScores;   // the score rows go by entry
+  __device__ int out_ld(const TileCoord&) const { return bsp; }
   __device__ size_t row_off(const TileCoord& tc, int tag, int m) const {
     return MODE == kTokScores ? (size_t)(tag - 1) * bs : (size_t)(tc.slot0 + m) * bsp;
   }
@@ -164,6 +168,8 @@ struct ProbTokNC {
   __device__ int out_cols(const TileCoord&) const { return d; }   // d % 64 == 0
   static constexpr bool kAux = false;
   __device__ int row_tag(const TileCoord& tc, int m) const { return m < tc.Mrows ? 1 : 0; }
+  static constexpr bool kRowsLinear = true;
+  __device__ int out_ld(const TileCoord&) const { return d; }
   __device__ size_t row_off(const TileCoord& tc, int, int m) const { return (size_t)(tc.slot0 + m) * d; }
   static constexpr bool kOutBf16 = true;
   __device__ void store_pk(size_t at, int, uint32_t pk, uint32_t) const { *reinterpret_cast<uint32_t*>(part + at) = pk; }
@@ -212,6 +218,8 @@ struct ProbNeuTN {
     return (m < bs && flag[(size_t)tc.g * bs + m] > 0) ? 1 : 0;
   }
   static constexpr bool kAux = false;
+  static constexpr bool kRowsLinear = true;
+  __device__ int out_ld(const TileCoord&) const { return d; }
   __device__ size_t row_off(const TileCoord& tc, int, int m) const { return ((size_t)tc.g * bs + m) * d; }
   static constexpr bool kOutBf16 = true;
   __device__ void store_pk(size_t at, int, uint32_t pk, uint32_t) const { *reinterpret_cast<uint32_t*>(G + at) = pk; }

@@ -104,6 +104,8 @@ struct TileCoord {
 //                before the k loop.
 //   __device__ size_t row_off(const TileCoord&, int tag, int m) const;   element offset of (row m, column 0) in
 //                the output array
+//   static constexpr bool kRowsLinear;   true: row_off does not depend on the tag and is linear in m with the step
+//                __device__ int out_ld(const TileCoord&) const;   (the kernel then multiplies once per tile)
 //   static constexpr bool kOutBf16;   the output is bf16 (the kernel converts, two columns to a word) or fp32
 //       false: __device__ void store2(size_t at, int n, float v0, float v1, uint32_t aux) const;   store C[m][n] = v0
 //                and C[m][n + 1] = v1 at element offset `at` (= row_off + n; n even, n < round-up of out_cols to 32;
@@ -504,78 +506,81 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       const bool odd = (lane & 1) != 0;
       const int nj = (p.out_cols(tc) - (tc.n0 + wn) + 31) / 32;   // 32-column fragments of this wave with stored columns
       const int ncol = tc.n0 + wn + (fr & ~1);
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        int tag[8];
-        uint32_t aux[8][4];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const int r = 2 * q;
-          const int rl = i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3) + (lane & 1);    // row inside the wave's 64
-          tag[q] = __builtin_amdgcn_ds_bpermute(rl << 2, my_tag);
-          if constexpr (P::kAux) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) aux[q][j] = p.load_aux(tc, tc.m0 + wm + rl, ncol + 32 * j);
-          } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) aux[q][j] = 0u;
-          }
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const int r = 2 * q;
-          const int rl = i * 32 + (r >> 2) * 8 + fc * 4 + (r & 3) + (lane & 1);
-          if constexpr (P::kOutBf16) {
-            // bf16 output: both rows' values of this lane's column are packed first, (row m | row m+1 << 16); one
-            // neighbour swap of the packed word and one byte permute give (column c | column c+1 << 16) of the
-            // lane's row (even lanes: row m from the low halves, odd lanes: row m+1 from the high halves)
-            const uint32_t sel = odd ? 0x03020706u : 0x05040100u;   // bytes 0-3: own word, 4-7: the neighbour's
-            uint32_t pk[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const uint32_t own = pack_bf16x2(acc[i][j][r], acc[i][j][r + 1]);
-              const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp((int)own, (int)own, 0xB1, 0xF, 0xF, true);
-              pk[j] = __builtin_amdgcn_perm(nb, own, sel);
-            }
-            if (tag[q] != 0) {
-              const size_t at = p.row_off(tc, tag[q], tc.m0 + wm + rl) + ncol;
-              if (nj >= 4) {
-                p.store_pk(at, ncol, pk[0], aux[q][0]);
-                p.store_pk(at + 32, ncol + 32, pk[1], aux[q][1]);
-                p.store_pk(at + 64, ncol + 64, pk[2], aux[q][2]);
-                p.store_pk(at + 96, ncol + 96, pk[3], aux[q][3]);
-              } else {
-                if (nj > 0) p.store_pk(at, ncol, pk[0], aux[q][0]);
-                if (nj > 1) p.store_pk(at + 32, ncol + 32, pk[1], aux[q][1]);
-                if (nj > 2) p.store_pk(at + 64, ncol + 64, pk[2], aux[q][2]);
-              }
-            }
-          } else {
-            float lo[4], hi[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
-              const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
-              const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
-              lo[j] = odd ? bn : a;
-              hi[j] = odd ? b : an;
-            }
-            if (tag[q] != 0) {
-              const size_t at = p.row_off(tc, tag[q], tc.m0 + wm + rl) + ncol;
-              if (nj >= 4) {
-                p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
-                p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
-                p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
-                p.store2(at + 96, ncol + 96, lo[3], hi[3], aux[q][3]);
-              } else {
-                if (nj > 0) p.store2(at, ncol, lo[0], hi[0], aux[q][0]);
-                if (nj > 1) p.store2(at + 32, ncol + 32, lo[1], hi[1], aux[q][1]);
-                if (nj > 2) p.store2(at + 64, ncol + 64, lo[2], hi[2], aux[q][2]);
-              }
-            }
-          }
-        }
+      // row of this lane inside the wave's 64 = lane_row + a constant of the register pair
+      const int lane_row = fc * 4 + (lane & 1);
+      [[maybe_unused]] size_t lane_at = 0;
+      [[maybe_unused]] int ld = 0;
+      if constexpr (P::kRowsLinear) {
+        ld = p.out_ld(tc);
+        lane_at = p.row_off(tc, 1, tc.m0 + wm + lane_row) + ncol;   // one multiplication per tile
       }
+      [[maybe_unused]] const unsigned long long ok_mask = __ballot(my_tag != 0);
+      auto epilogue = [&](auto full_tag) {
+        constexpr bool kFull = decltype(full_tag)::value;   // all four fragments of the wave lie inside the output
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          int tag[8];
+          uint32_t aux[8][4];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const int r = 2 * q;
+            const int rl = i * 32 + (r >> 2) * 8 + (r & 3) + lane_row;
+            // the row's tag: a bit of the wave's ballot where it only says "stored or not" (no trip through the LDS
+            // pipeline, which the loaders keep busy), a lane permute where it carries a number
+            if constexpr (P::kRowsLinear) tag[q] = (int)((ok_mask >> rl) & 1ull);
+            else tag[q] = __builtin_amdgcn_ds_bpermute(rl << 2, my_tag);
+            if constexpr (P::kAux) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) aux[q][j] = p.load_aux(tc, tc.m0 + wm + rl, ncol + 32 * j);
+            } else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) aux[q][j] = 0u;
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const int r = 2 * q;
+            const int rc = i * 32 + (r >> 2) * 8 + (r & 3);   // the register pair's constant part of the row
+            [[maybe_unused]] uint32_t pk[4];
+            [[maybe_unused]] float lo[4], hi[4];
+            if constexpr (P::kOutBf16) {
+              // bf16 output: both rows' values of this lane's column are packed first, (row m | row m+1 << 16); one
+              // neighbour swap of the packed word and one byte permute give (column c | column c+1 << 16) of the
+              // lane's row (even lanes: row m from the low halves, odd lanes: row m+1 from the high halves)
+              const uint32_t sel = odd ? 0x03020706u : 0x05040100u;   // bytes 0-3: own word, 4-7: the neighbour's
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const uint32_t own = pack_bf16x2(acc[i][j][r], acc[i][j][r + 1]);
+                const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp((int)own, (int)own, 0xB1, 0xF, 0xF, true);
+                pk[j] = __builtin_amdgcn_perm(nb, own, sel);
+              }
+            } else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
+                const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
+                const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
+                lo[j] = odd ? bn : a;
+                hi[j] = odd ? b : an;
+              }
+            }
+            if (tag[q] != 0) {
+              size_t at;
+              if constexpr (P::kRowsLinear) at = lane_at + (size_t)(rc * ld);   // rc * ld: scalar arithmetic
+              else at = p.row_off(tc, tag[q], tc.m0 + wm + rc + lane_row) + ncol;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                if (kFull || j < nj) {
+                  if constexpr (P::kOutBf16) p.store_pk(at + 32 * j, ncol + 32 * j, pk[j], aux[q][j]);
+                  else p.store2(at + 32 * j, ncol + 32 * j, lo[j], hi[j], aux[q][j]);
+                }
+              }
+            }
+          }
+        }
+      };
+      if (nj >= 4) epilogue(std::true_type{});
+      else epilogue(std::false_type{});
     }
     if (!more) break;
     tc = tn;
