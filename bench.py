@@ -53,10 +53,10 @@ def kernel_models(cfg):
 
 # profiler name of the kernel behind each stage label (the rocprofv3 summaries list kernels by symbol)
 STAGE_SYMBOL = {
-    "router_gemm": "gemm_mfma_kernel<ProbRouter>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<0> >",
-    "dact_gemm": "gemm_mfma_kernel<ProbTokKC<1> >", "value_gemm": "gemm_mfma_kernel<ProbTokNC>",
-    "dh_gemm": "gemm_mfma_kernel<ProbTokNC>", "dV_gemm": "gemm_mfma_kernel<ProbNeuTN>",
-    "dK_gemm": "gemm_mfma_kernel<ProbNeuTN>", "topk_select": "topk_select_reg_kernel<16>", "reduce_parts": "reduce_parts_kernel<2>",
+    "router_gemm": "gemm_mfma_kernel<ProbRouter, true>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<0>, true>",
+    "dact_gemm": "gemm_mfma_kernel<ProbTokKC<1>, true>", "value_gemm": "gemm_mfma_kernel<ProbTokNC, true>",
+    "dh_gemm": "gemm_mfma_kernel<ProbTokNC, true>", "dV_gemm": "gemm_mfma_kernel<ProbNeuTN, true>",
+    "dK_gemm": "gemm_mfma_kernel<ProbNeuTN, true>", "topk_select": "topk_select_reg_kernel<16>", "reduce_parts": "reduce_parts_kernel<2>",
 }
 
 

@@ -37,6 +37,9 @@ struct ProbRouter {
   static constexpr bool kRowIdsInMemory = false;
   const uint16_t* h; const uint16_t* Wg; float* p;
   int T, d, B, ksplit;
+  uint32_t a_bytes, b_bytes; bool buf;
+  __device__ const uint16_t* a_base() const { return h; }
+  __device__ const uint16_t* b_base() const { return Wg; }
   __device__ bool locate(int wg, TileCoord& tc) const {
     const int tn = (B + kTN - 1) / kTN;
     const int ks = wg % ksplit, w = wg / ksplit, mt = w / tn;
@@ -85,6 +88,9 @@ struct ProbTokKC {
   float* sc;                  // kTokScores: [T*e, bs]
   const uint16_t* Ap;         // kTokMasked: A' [slots, bsp]
   uint16_t* DS;               // kTokMasked / kTokRelu: [slots, bsp]; columns bs..bsp are written as zeros
+  uint32_t a_bytes, b_bytes; bool buf;
+  __device__ const uint16_t* a_base() const { return X; }
+  __device__ const uint16_t* b_base() const { return W; }
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
     if (!locate_token_tile(sched, group_off, wg, (bs + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
@@ -154,6 +160,9 @@ struct ProbTokNC {
   TokenSched sched;
   int bs, bsp, d;
   uint16_t* part;             // [slots, d] bf16: one block's contribution to a token's row
+  uint32_t a_bytes, b_bytes; bool buf;
+  __device__ const uint16_t* a_base() const { return A; }
+  __device__ const uint16_t* b_base() const { return W; }
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
     if (!locate_token_tile(sched, group_off, wg, (d + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
@@ -194,6 +203,9 @@ struct ProbNeuTN {
   TokenSched sched;           // only the group lists are used: every group has the same number of tiles
   int bs, bsp, d;
   uint16_t* G;                // dV or dK [N, d]
+  uint32_t a_bytes, b_bytes; bool buf;
+  __device__ const uint16_t* a_base() const { return A + (int64_t)zrow * bsp; }   // the row of zeros lies lowest
+  __device__ const uint16_t* b_base() const { return X; }
   __device__ bool locate(int wg, TileCoord& tc) const {
     const int tm = (bs + kTM - 1) / kTM, tn = (d + kTN - 1) / kTN;
     const int x = wg & (kXcd - 1), local = wg >> 3;

@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -426,18 +427,37 @@ void launch_seg_reduce(const meft_shape& s, const BwdWs& w, const int32_t* touch
 
 constexpr int kPersistentWgs = 256;   // compute units of an MI355X; a multiple of the 8 XCDs
 
+// Bytes readable from an operand's lowest address; buffer loads (32-bit offsets) where both fit.  Setting
+// MEFT_GLOBAL_LOADS=1 in the environment selects the global-load kernels (those for operands of 4 GB and more)
+// at any size, so that tests reach them with small inputs.
+template <class P>
+void set_gemm_extents(P& p, uint64_t a_bytes, uint64_t b_bytes) {
+  constexpr uint64_t kLimit = 0xFFFF0000ull;
+  const char* env = getenv("MEFT_GLOBAL_LOADS");
+  const bool forced_global = env && env[0] == '1';
+  p.buf = !forced_global && a_bytes < kLimit && b_bytes < kLimit;
+  p.a_bytes = p.buf ? (uint32_t)a_bytes : 0u;
+  p.b_bytes = p.buf ? (uint32_t)b_bytes : 0u;
+}
+
 template <class P>
 void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st) {
-  static bool configured = false;  // raise the dynamic LDS limit of this instantiation once
+  static bool configured = false;  // raise the dynamic LDS limit of both instantiations once
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P, true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
     configured = true;
   }
   // persistent workgroups: one per compute unit (the LDS footprint allows no more), each walking the tile ids
   // wg, wg + 256, ... below `grid`
   const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
-  MEFT_LAUNCH(name, (gemm_mfma_kernel<P>), dim3(launch), dim3(gemm_threads<P>()), kGemmLdsBytes, st, prob, grid);
+  if (prob.buf) {
+    MEFT_LAUNCH(name, (gemm_mfma_kernel<P, true>), dim3(launch), dim3(gemm_threads<P>()), kGemmLdsBytes, st, prob, grid);
+  } else {
+    MEFT_LAUNCH(name, (gemm_mfma_kernel<P, false>), dim3(launch), dim3(gemm_threads<P>()), kGemmLdsBytes, st, prob, grid);
+  }
 }
 
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
@@ -503,6 +523,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokKC<kTokScores> ps{};
     ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.sched = sched;
     ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
+    set_gemm_extents(ps, (uint64_t)s.T * s.d * 2, (uint64_t)s.N * s.d * 2);
     launch_gemm_mfma("score_gemm", ps, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
   } else {
     GemmNTArgs a{};
@@ -542,6 +563,7 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokNC pv{};
     pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
     pv.d = s.d; pv.part = w.part;
+    set_gemm_extents(pv, (uint64_t)n_ent * bsp * 2, (uint64_t)s.N * s.d * 2);
     launch_gemm_mfma("value_gemm", pv, tile_bound(s, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(s, w.part, w, out, st);
   } else if (s.dtype == MEFT_BF16) {
@@ -587,17 +609,20 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
     // gathers the same dOut rows as the activation-gradient GEMM that follows it
     pn.A = w.Ap; pn.zrow = -1; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
+    set_gemm_extents(pn, (uint64_t)(1 + 2 * (uint64_t)n_ent) * bsp * 2, (uint64_t)s.T * s.d * 2);
     launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<kTokMasked> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
     pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS;
+    set_gemm_extents(pg, (uint64_t)s.T * s.d * 2, (uint64_t)s.N * s.d * 2);
     launch_gemm_mfma("dact_gemm", pg, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
     if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     if (dh) {
       ProbTokNC ph{};
       ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
       ph.d = s.d; ph.part = w.part;
+      set_gemm_extents(ph, (uint64_t)n_ent * bsp * 2, (uint64_t)s.N * s.d * 2);
       launch_gemm_mfma("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
@@ -650,6 +675,7 @@ static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& 
   pr.X = static_cast<const uint16_t*>(h); pr.W = w.Kc; pr.perm = w.perm; pr.group_off = w.group_off;
   pr.sched = sched; pr.e = g.nvb; pr.bs = g.vbs; pr.bsp = g.vbs; pr.d = s.d;
   pr.DS = w.Ap;
+  set_gemm_extents(pr, (uint64_t)s.T * s.d * 2, (uint64_t)n_rows * s.d * 2);
   launch_gemm_mfma("union_score_gemm", pr, tile_bound(g.vs, (g.vbs + kTN - 1) / kTN), st);
 }
 
@@ -692,6 +718,7 @@ meft_status meft_union_fwd(const meft_shape* shape, const void* h, const void* K
   ProbTokNC pv{};
   pv.A = w.Ap; pv.W = w.Vc; pv.group_off = w.group_off; pv.sched = sched; pv.bs = g.vbs; pv.bsp = g.vbs;
   pv.d = s.d; pv.part = w.part;
+  set_gemm_extents(pv, (uint64_t)s.T * g.nvb * g.vbs * 2, (uint64_t)g.nvb * g.vbs * s.d * 2);
   launch_gemm_mfma("union_value_gemm", pv, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
   launch_reduce_parts(g.vs, w.part, w, out, st);
   return launch_status();
@@ -720,11 +747,13 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   ProbTokKC<kTokMasked> pg{};
   pg.X = gg; pg.W = w.Vc; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
   pg.e = g.nvb; pg.bs = g.vbs; pg.bsp = g.vbs; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS;
+  set_gemm_extents(pg, (uint64_t)s.T * s.d * 2, (uint64_t)g.nvb * g.vbs * s.d * 2);
   launch_gemm_mfma("union_dact_gemm", pg, tile_bound(g.vs, (g.vbs + kTN - 1) / kTN), st);
   if (dh) {
     ProbTokNC ph{};
     ph.A = w.DS; ph.W = w.Kc; ph.group_off = w.group_off; ph.sched = sched; ph.bs = g.vbs; ph.bsp = g.vbs;
     ph.d = s.d; ph.part = w.part;
+    set_gemm_extents(ph, (uint64_t)s.T * g.nvb * g.vbs * 2, (uint64_t)g.nvb * g.vbs * s.d * 2);
     launch_gemm_mfma("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(g.vs, w.part, w, dh, st);
   }
@@ -734,6 +763,7 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;
   pn.sched = sched; pn.bs = g.vbs; pn.bsp = g.vbs; pn.d = s.d;
   pn.A = w.Ap; pn.zrow = -1; pn.X = gg; pn.G = w.dVc;
+  set_gemm_extents(pn, (1 + 2 * (uint64_t)s.T * g.nvb) * g.vbs * 2, (uint64_t)s.T * s.d * 2);
   launch_gemm_mfma("union_dV_gemm", pn, neu_grid, st);
   pn.A = w.DS; pn.zrow = -(s.T * g.nvb + 1); pn.X = hh; pn.G = w.dKc;
   launch_gemm_mfma("union_dK_gemm", pn, neu_grid, st);
@@ -780,6 +810,7 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
     const int kt = s.d / kTK;
     n_part = kt % 4 == 0 ? 4 : (kt % 2 == 0 ? 2 : 1);
     ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), w.p, s.T, s.d, s.n_blocks, n_part};
+    set_gemm_extents(pr, (uint64_t)s.T * s.d * 2, (uint64_t)s.n_blocks * s.d * 2);
     launch_gemm_mfma("router_gemm", pr, n_part * ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
   } else {
     GemmNTArgs a{};

@@ -93,3 +93,12 @@ def test_everything_selected_on_the_matrix_core_path():
     assert P.rel_l2(g["out"], dense_ref.dense_adapter(t.h, t.K, t.V)) <= 2e-2
     dh, dK, dV = dense_ref.dense_adapter_grads(t.h, t.K, t.V, t.dOut)
     assert P.rel_l2(g["dh"], dh) <= 2e-2 and P.rel_l2(g["dK"], dK) <= 2e-2 and P.rel_l2(g["dV"], dV) <= 2e-2
+
+
+def test_global_load_kernels_match_the_buffer_load_kernels(monkeypatch):
+    """The matrix-core kernels load operands below 4 GB through buffer resources and larger ones through global
+    pointers; MEFT_GLOBAL_LOADS=1 selects the latter at any size.  Both give the same bits."""
+    t = synth.make_inputs(synth.small_case(**CASES[1]))
+    ref = P.run_gpu(t)
+    monkeypatch.setenv("MEFT_GLOBAL_LOADS", "1")
+    _same(ref, P.run_gpu(t))
