@@ -173,6 +173,8 @@ struct ProbTokNC {
     return A + (size_t)(tc.slot0 + (m < tc.Mrows ? m : tc.Mrows - 1)) * bsp;
   }
   __device__ int b_row_ids(const TileCoord& tc, int k) const { return tc.g * bs + (k < bs ? k : bs - 1); }
+  // the 64 rows from k0 on are consecutive rows of W (no clamping inside the k tile)
+  __device__ bool b_rows_linear(const TileCoord&, int k0) const { return k0 + kTK <= bs; }
   __device__ const uint16_t* b_row_ptr(int row) const { return W + (size_t)row * d; }
   __device__ int out_cols(const TileCoord&) const { return d; }   // d % 64 == 0
   static constexpr bool kAux = false;

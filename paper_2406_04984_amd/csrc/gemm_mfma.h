@@ -179,6 +179,10 @@ __device__ __forceinline__ void tr_read12(u32x2 (&oa)[4], u32x2 (&ob)[8], const 
 // MFMAs keeps neither queue full.  The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ...
 // (gridDim.x is a multiple of 8, so it stays on one XCD's list).
 // kBuf: the operand loads are buffer loads (both operand matrices smaller than 4 GB) instead of global loads
+__device__ __forceinline__ uint32_t byte_off(const uint16_t* ptr, const uint16_t* base) {
+  return (uint32_t)(reinterpret_cast<uintptr_t>(ptr) - reinterpret_cast<uintptr_t>(base));
+}
+
 template <class P, bool kBuf>
 __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
   constexpr int kLoaders = P::kLoaders;
@@ -230,8 +234,42 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     // set up that many bytes lower.
     const uint16_t* pa[P::kAMC ? 4 : LA];   // m-contiguous: row 0 at this lane's column, one per offset 0..3 KB
     const uint16_t* pb[P::kBNC ? 4 : LB];
+    // Buffer loads (kBuf): the same addresses as 32-bit byte offsets from the operand's lowest address, without the
+    // kilobyte shifts (every load writes M0, a scalar instruction).  Whatever is the same in all lanes goes into the
+    // instruction's scalar offset: the k offset of k-contiguous operands, the row offset of consecutive B rows.
+    [[maybe_unused]] uint32_t oa[P::kAMC ? 4 : LA], ob[P::kBNC ? 4 : LB];
     const int half = lane >> 5;
     auto setup = [&]() {
+      if constexpr (kBuf) {
+        if constexpr (P::kAMC) {
+          const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
+          const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
+          const uint32_t o = byte_off(p.a_mat() + (col > last ? last : col), p.a_base());
+#pragma unroll
+          for (int q = 0; q < 4; ++q) oa[q] = o;
+        } else {
+#pragma unroll
+          for (int i = 0; i < LA; ++i) {
+            const int row = (lw * LA + i) * 8 + lr8;
+            oa[i] = byte_off(p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3), p.a_base());
+          }
+        }
+        if constexpr (P::kBNC) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
+            int col = t_o.n0 + chunk * 8;
+            col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;
+            ob[q] = byte_off(p.b_row_ptr(0) + col, p.b_base());
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < LB; ++i) {
+            const int row = (lw * LB + i) * 8 + lr8;
+            ob[i] = byte_off(p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3), p.b_base());
+          }
+        }
+      } else {
       if constexpr (P::kAMC) {
         const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
         const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
@@ -260,11 +298,12 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
           pb[i] = p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
         }
       }
+      }
     };
-    // Where every operand matrix is smaller than 4 GB the loads are buffer loads instead (a wave-uniform resource
-    // descriptor and a 32-bit offset per lane instead of a 64-bit address per lane): the vector-memory path takes
-    // them faster (score GEMM 0.331 -> 0.314 ms).  Their offset is the same address minus the matrix's start.
-    constexpr bool use_buf = kBuf;
+    // Where every operand matrix is smaller than 4 GB the loads are buffer loads (a wave-uniform resource descriptor,
+    // a 32-bit offset per lane and a scalar offset instead of a 64-bit address per lane): the vector-memory path
+    // takes them faster (score GEMM 0.331 -> 0.314 ms), and a load of the k-contiguous problems then costs the
+    // loader a write of M0 and nothing else.
     __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.a_base()), 0, (int)p.a_bytes, 0x00020000);
     __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.b_base()), 0, (int)p.b_bytes, 0x00020000);
     // load number i of a loader into the 1 KB slot i of its part of an operand region (see above)
@@ -280,11 +319,11 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       default: __builtin_amdgcn_global_load_lds(g_, l_, 16, 3072, 0); break;            \
     }                                                                                   \
   } while (0)
-    // the same load as a buffer load: `src` is the pointer the global load would use (set up (i & 3) KB low)
-#define MEFT_LOAD_1K_BUF(rsrc, base, src, region, i)                                                            \
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                                     \
-      rsrc, MEFT_LPTR((region) + (i) * 512), 16,                                                                \
-      (uint32_t)(reinterpret_cast<uintptr_t>(src) - reinterpret_cast<uintptr_t>(base)) + ((i) & 3) * 1024u, 0, 0, 0)
+    // buffer load number i: lane offset `voff`, wave-uniform offset `soff` (bytes).  The casts are needed: handed an
+    // unsigned offset, this toolchain's host pass drops the kernel's launch stub without any diagnostic and the
+    // library then fails to load with an undefined symbol.
+#define MEFT_LOAD_1K_BUF(rsrc, voff, soff, region, i) \
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, MEFT_LPTR((region) + (i) * 512), 16, (int)(voff), (int)(soff), 0, 0)
 
     auto request_ids = [&]() {
       if constexpr (P::kBNC && P::kRowIdsInMemory) {
@@ -339,33 +378,57 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       if constexpr (P::kAMC) a_row_bytes = p.a_cols(t_o) * 2;
       uint16_t* my_a = sa + lw * LA * 512;   // 512 elements = 1 KB per load
       uint16_t* my_b = sb + lw * LB * 512;
-      const uint16_t* a0 = p.a_base();
-      const uint16_t* b0 = p.b_base();
+      if constexpr (kBuf) {
+        const int k_bytes = k_o * kTK * 2;
 #pragma unroll
-      for (int i = 0; i < LA; ++i) {
-        if constexpr (P::kAMC) {
-          const int row = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4));
-          const char* src = reinterpret_cast<const char*>(pa[i & 3]) + (int64_t)row * a_row_bytes;
-          if constexpr (use_buf) MEFT_LOAD_1K_BUF(rsrc_a, a0, src, my_a, i);
-          else MEFT_LOAD_1K(src, my_a, i);
-        } else {
-          if constexpr (use_buf) MEFT_LOAD_1K_BUF(rsrc_a, a0, pa[i] + k_o * kTK, my_a, i);
-          else MEFT_LOAD_1K(pa[i] + k_o * kTK, my_a, i);
+        for (int i = 0; i < LA; ++i) {
+          if constexpr (P::kAMC) {
+            const int row = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4));
+            MEFT_LOAD_1K_BUF(rsrc_a, oa[i & 3] + (uint32_t)row * (uint32_t)a_row_bytes, 0, my_a, i);
+          } else {
+            MEFT_LOAD_1K_BUF(rsrc_a, oa[i], k_bytes, my_a, i);
+          }
         }
-      }
-      if constexpr (P::kBNC) {
-        const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
+        if constexpr (P::kBNC) {
+          const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
+          bool linear = false;
+          if constexpr (!P::kRowIdsInMemory) {
+            linear = p.b_rows_linear(t_o, k_o * kTK);
+            if (linear) {
+              // 64 consecutive rows: this lane's row is first + 2 * (lw * LB + i) + half
+              const uint32_t first = (uint32_t)p.b_row_ids(t_o, k_o * kTK) * row_bytes, hoff = half * row_bytes;
 #pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          const char* src = reinterpret_cast<const char*>(pb[i & 3]) + (uint64_t)(uint32_t)ids[i] * row_bytes;
-          if constexpr (use_buf) MEFT_LOAD_1K_BUF(rsrc_b, b0, src, my_b, i);
-          else MEFT_LOAD_1K(src, my_b, i);
+              for (int i = 0; i < LB; ++i)
+                MEFT_LOAD_1K_BUF(rsrc_b, ob[i & 3] + hoff, (int)(first + 2u * (lw * LB + i) * row_bytes), my_b, i);
+            }
+          }
+          if (!linear) {
+#pragma unroll
+            for (int i = 0; i < LB; ++i)
+              MEFT_LOAD_1K_BUF(rsrc_b, ob[i & 3] + (uint32_t)ids[i] * row_bytes, 0, my_b, i);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < LB; ++i) MEFT_LOAD_1K_BUF(rsrc_b, ob[i], k_bytes, my_b, i);
         }
       } else {
 #pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          if constexpr (use_buf) MEFT_LOAD_1K_BUF(rsrc_b, b0, pb[i] + k_o * kTK, my_b, i);
-          else MEFT_LOAD_1K(pb[i] + k_o * kTK, my_b, i);
+        for (int i = 0; i < LA; ++i) {
+          if constexpr (P::kAMC) {
+            const int row = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4));
+            MEFT_LOAD_1K(reinterpret_cast<const char*>(pa[i & 3]) + (int64_t)row * a_row_bytes, my_a, i);
+          } else {
+            MEFT_LOAD_1K(pa[i] + k_o * kTK, my_a, i);
+          }
+        }
+        if constexpr (P::kBNC) {
+          const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
+#pragma unroll
+          for (int i = 0; i < LB; ++i)
+            MEFT_LOAD_1K(reinterpret_cast<const char*>(pb[i & 3]) + (uint64_t)(uint32_t)ids[i] * row_bytes, my_b, i);
+        } else {
+#pragma unroll
+          for (int i = 0; i < LB; ++i) MEFT_LOAD_1K(pb[i] + k_o * kTK, my_b, i);
         }
       }
       ++n_o;
