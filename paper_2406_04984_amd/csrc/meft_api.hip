@@ -537,13 +537,15 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
   if (C <= kMaxLdsC) {
     // keys in registers, the smallest per-thread count that covers the C candidates with 256 threads
     uint16_t* ap = dense ? w.Ap : nullptr;
-#define TK(KPT) MEFT_LAUNCH("topk_select", (topk_select_reg_kernel<KPT>), dim3(s.T), dim3(256), 0, st, w.sc, w.sblk, C, s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, ap)
+#define TK2(KPT, FULL) MEFT_LAUNCH("topk_select", (topk_select_reg_kernel<KPT, FULL>), dim3(s.T), dim3(256), 0, st, w.sc, w.sblk, C, s.block_size, s.top_e, s.top_k, idx, act, w.slot_of_ent, bsp, ap)
+#define TK(KPT) do { if (C == 256 * (KPT)) TK2(KPT, true); else TK2(KPT, false); } while (0)
     if (C <= 256 * 4) TK(4);
     else if (C <= 256 * 8) TK(8);
     else if (C <= 256 * 16) TK(16);
     else if (C <= 256 * 32) TK(32);
     else TK(48);
 #undef TK
+#undef TK2
   }
   else if (C <= 1024 * 64) {
     // e.g. one block holding every neuron: 1024 threads per token, still with the keys in registers

@@ -155,12 +155,19 @@ __global__ __launch_bounds__(1024) void fill_groups_kernel(const int32_t* __rest
 //
 // The token's keys live in registers: thread `tid` owns the KPT consecutive candidate
 // positions tid*KPT .. tid*KPT + KPT - 1 (256 * KPT >= C), reads them once from global memory and keeps their
-// ordered keys for all four histogram passes, the ordered sweep and the dense activation rows.  LDS only holds
-// the 256-bin histogram; a thread adds runs of equal digits with one atomic, which takes most of the
-// same-address conflicts out of the first pass (sign and exponent bits: a handful of distinct digits).
+// ordered keys for all histogram passes, the ordered sweep and the dense activation rows.  LDS holds the 256-bin
+// histogram (a thread adds runs of equal digits with one atomic, which takes most of the same-address conflicts out
+// of the first pass: sign and exponent bits, a handful of distinct digits) and the staging arrays of the outputs.
+// The passes stop as soon as a whole bucket is selected (usually after three).  The kernel is bound by its
+// instruction count, not by memory: nested branches, per-position integer divisions and nearly empty global stores
+// were what it spent its time on.
 // ---------------------------------------------------------------------------------------------
-template <int KPT>
-__global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __restrict__ sc,
+constexpr int kTopkEmitLds = 1024;   // selections per token that go through LDS in one round
+
+// Seven waves per SIMD (72 registers): measured best at 16 keys per thread (0.095 ms against 0.102 with the 86
+// registers the compiler takes unasked, 0.118 at six waves, 0.123 at eight)
+template <int KPT, bool kFull>   // kFull: C == 256 * KPT, every position holds a candidate
+__global__ __launch_bounds__(256, 7) void topk_select_reg_kernel(const float* __restrict__ sc,
                                                               const int32_t* __restrict__ sblk, int C, int bs,
                                                               int e, int k, int32_t* __restrict__ idx,
                                                               float* __restrict__ act,
@@ -170,6 +177,11 @@ __global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __res
   __shared__ int s_w[4];
   __shared__ uint32_t s_prefix;
   __shared__ int s_need;
+  __shared__ int s_done;
+  // staging for the outputs: the sweep reaches a selected position in a few lanes at a time, and that many nearly
+  // empty global stores would cost more than everything before them
+  __shared__ int s_idx[kTopkEmitLds];
+  __shared__ float s_act[kTopkEmitLds];
   const int t = blockIdx.x, tid = threadIdx.x;
   const float* row = sc + (size_t)t * C;
   const int p0 = tid * KPT;
@@ -188,7 +200,7 @@ __global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __res
 #pragma unroll
     for (int z = 0; z < KPT; ++z) key[z] = p0 + z < C ? order_key(row[p0 + z]) : 0u;
   }
-  if (tid == 0) { s_prefix = 0u; s_need = k; }
+  if (tid == 0) { s_prefix = 0u; s_need = k; s_done = 0; }
   __syncthreads();
 
   for (int shift = 24; shift >= 0; shift -= 8) {
@@ -196,21 +208,21 @@ __global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __res
     __syncthreads();
     const uint32_t prefix = s_prefix;
     const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    int cur = -1, cnt = 0;
+    // A thread adds a run of equal digits with one atomic (that takes most of the same-address conflicts out of the
+    // first pass).  Written without nested branches: a run ends where a matching key has another digit; the first
+    // "run" is an empty one of digit 0, whose add of zero is harmless.
+    uint32_t cur = 0u;
+    int cnt = 0;
 #pragma unroll
     for (int z = 0; z < KPT; ++z) {
-      if (p0 + z < C && (key[z] & himask) == prefix) {
-        const int dgt = (int)((key[z] >> shift) & 255u);
-        if (dgt == cur) {
-          ++cnt;
-        } else {
-          if (cnt) atomicAdd(&s_hist[cur], cnt);
-          cur = dgt;
-          cnt = 1;
-        }
-      }
+      const bool m = (kFull || p0 + z < C) && (key[z] & himask) == prefix;
+      const uint32_t dgt = (key[z] >> shift) & 255u;
+      const bool start = m && dgt != cur;
+      if (start) atomicAdd(&s_hist[cur], cnt);
+      cnt = (start ? 0 : cnt) + (m ? 1 : 0);
+      cur = start ? dgt : cur;
     }
-    if (cnt) atomicAdd(&s_hist[cur], cnt);
+    atomicAdd(&s_hist[cur], cnt);
     __syncthreads();
     // thread `tid` owns digit 255 - tid, so that an exclusive scan counts the larger digits
     const int digit = 255 - tid;
@@ -220,60 +232,85 @@ __global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __res
     const int need = s_need;
     __syncthreads();
     if (above < need && need <= above + h) {
-      s_prefix = prefix | ((uint32_t)digit << shift);
-      s_need = need - above;
+      const uint32_t found = prefix | ((uint32_t)digit << shift);
+      if (h == need - above && shift > 0 && found != 0u) {
+        // every key with these leading digits is selected: "greater than found - 1" says the same as a threshold
+        // with all digits known, and the remaining passes are not needed (the usual case after three passes)
+        s_prefix = found - 1u;
+        s_need = 0;
+        s_done = 1;
+      } else {
+        s_prefix = found;
+        s_need = need - above;
+      }
     }
     __syncthreads();
+    if (s_done) break;
   }
   const uint32_t thr = s_prefix;
-  const int need = s_need;  // how many keys equal to thr are selected (>= 1)
+  const int need = s_need;  // how many keys equal to thr are selected
 
   int ngt = 0, neq = 0;
 #pragma unroll
   for (int z = 0; z < KPT; ++z) {
     ngt += key[z] > thr;               // padding keys are 0 <= thr's lower bound: never greater
-    neq += (p0 + z < C) && key[z] == thr;
+    neq += (kFull || p0 + z < C) && key[z] == thr;
   }
   int tot;
   const int packed = block_excl_scan_256(ngt | (neq << 16), s_w, tot);  // C <= 12288 < 2^15
   int gt_before = packed & 0xFFFF, eq_before = packed >> 16;
   uint32_t sel = 0u;   // bit z: position p0 + z is selected (KPT <= 32 bits used per word)
   uint32_t sel_hi = 0u;
+  const int q0 = p0 / bs, r0 = p0 - q0 * bs;   // block entry and row of the thread's first position
+  // The selected (position, key) pairs go to their output slots through LDS, kTopkEmitLds slots at a time (one round
+  // unless top_k is larger than that); the write-out turns a position into a neuron number and a key into max(score, 0).
+  for (int base = 0; base < k; base += kTopkEmitLds) {
+    int gt_run = gt_before, eq_run = eq_before;
 #pragma unroll
-  for (int z = 0; z < KPT; ++z) {
-    const bool in = p0 + z < C;
-    const bool gt = key[z] > thr, eq = in && key[z] == thr;
-    if (gt || (eq && eq_before < need)) {
-      const int slot = gt_before + min(eq_before, need);  // selected positions before this one
-      const int i = p0 + z;
-      const int q = i / bs, r = i - q * bs;
-      const float v = key_to_float(key[z]);
-      idx[(size_t)t * k + slot] = sblk[(size_t)t * e + q] * bs + r;
-      act[(size_t)t * k + slot] = v > 0.f ? v : 0.f;
-      if (z < 32) sel |= 1u << z; else sel_hi |= 1u << (z - 32);
+    for (int z = 0; z < KPT; ++z) {
+      const bool in = kFull || p0 + z < C;
+      const bool gt = key[z] > thr, eq = in && key[z] == thr;
+      if (gt || (eq && eq_run < need)) {
+        const int slot = gt_run + min(eq_run, need) - base;  // selected positions before this one
+        if ((unsigned)slot < (unsigned)kTopkEmitLds) {
+          s_idx[slot] = p0 + z;
+          s_act[slot] = __uint_as_float(key[z]);
+        }
+        if (z < 32) sel |= 1u << z; else sel_hi |= 1u << (z - 32);
+      }
+      gt_run += gt;
+      eq_run += eq;
     }
-    gt_before += gt;
-    eq_before += eq;
+    __syncthreads();
+    const int n_out = min(k - base, kTopkEmitLds);
+    for (int j = tid; j < n_out; j += 256) {
+      const int i = s_idx[j], q = i / bs;
+      const float v = key_to_float(__float_as_uint(s_act[j]));
+      idx[(size_t)t * k + base + j] = sblk[(size_t)t * e + q] * bs + (i - q * bs);
+      act[(size_t)t * k + base + j] = v > 0.f ? v : 0.f;
+    }
+    if (base + kTopkEmitLds < k) __syncthreads();   // the next round overwrites the staging arrays
   }
   if (Ap == nullptr) return;
   // dense activation rows A'[slot, 0:bsp] for the matrix-core path: bf16(act) where selected, else 0
-  uint16_t a16[KPT];
+  // a selected key of a positive score has its top bit set and the score's bits below it; everything else gives 0
+  float a32[KPT];
 #pragma unroll
   for (int z = 0; z < KPT; ++z) {
-    const bool on = z < 32 ? ((sel >> z) & 1u) : ((sel_hi >> (z - 32)) & 1u);
-    const float v = on ? key_to_float(key[z]) : 0.f;
-    a16[z] = (uint16_t)(v > 0.f ? f32_to_bf16_bits(v) : 0u);
+    const uint32_t on = z < 32 ? (uint32_t)__builtin_amdgcn_sbfe((int)sel, z, 1)
+                               : (uint32_t)__builtin_amdgcn_sbfe((int)sel_hi, z - 32, 1);
+    const uint32_t pos = (uint32_t)((int)key[z] >> 31);
+    a32[z] = __uint_as_float(key[z] & 0x7FFFFFFFu & on & pos);
   }
   if (bs % KPT == 0 && (KPT & 7) == 0) {
     // the thread's positions lie in one block's row, 16-byte aligned
     if (p0 < C) {
-      const int q = p0 / bs, r0 = p0 - q * bs;
-      uint16_t* dst = Ap + (size_t)slot_of_ent[t * e + q] * bsp + r0;
+      uint16_t* dst = Ap + (size_t)slot_of_ent[(size_t)t * e + q0] * bsp + r0;
 #pragma unroll
       for (int z = 0; z < KPT; z += 8) {
         u32x4 w;
-        w.x = a16[z] | ((uint32_t)a16[z + 1] << 16); w.y = a16[z + 2] | ((uint32_t)a16[z + 3] << 16);
-        w.z = a16[z + 4] | ((uint32_t)a16[z + 5] << 16); w.w = a16[z + 6] | ((uint32_t)a16[z + 7] << 16);
+        w.x = pack_bf16x2(a32[z], a32[z + 1]); w.y = pack_bf16x2(a32[z + 2], a32[z + 3]);
+        w.z = pack_bf16x2(a32[z + 4], a32[z + 5]); w.w = pack_bf16x2(a32[z + 6], a32[z + 7]);
         *reinterpret_cast<u32x4*>(dst + z) = w;
       }
     }
@@ -282,16 +319,16 @@ __global__ __launch_bounds__(256) void topk_select_reg_kernel(const float* __res
     for (int z = 0; z < KPT; ++z) {
       const int i = p0 + z;
       if (i < C) {
-        const int q = i / bs, r = i - q * bs;
-        Ap[(size_t)slot_of_ent[t * e + q] * bsp + r] = a16[z];
+        const int qz = i / bs, rz = i - qz * bs;
+        Ap[(size_t)slot_of_ent[t * e + qz] * bsp + rz] = (uint16_t)f32_to_bf16_bits(a32[z]);
       }
     }
   }
   // the padding columns bs .. bsp - 1 of the token's rows are zero
   const int pad = bsp - bs;
   for (int j = tid; j < e * pad; j += 256) {
-    const int q = j / pad, r = bs + (j - q * pad);
-    Ap[(size_t)slot_of_ent[t * e + q] * bsp + r] = 0;
+    const int qz = j / pad, rz = bs + (j - qz * pad);
+    Ap[(size_t)slot_of_ent[t * e + qz] * bsp + rz] = 0;
   }
 }
 

@@ -96,6 +96,32 @@ def test_degenerate_selections(P, dtype):
     _case(P, T=40, d=8, n_blocks=48, block_size=1, top_e=6, top_k=6, dtype=dtype, seed=206)     # one neuron per expert
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_selection_larger_than_one_output_staging_round(P, dtype):
+    """top_k beyond the 1024 selections that the selection kernel stages per round, candidate counts on and off the
+    kernel's 256 x keys-per-thread grid."""
+    _case(P, T=21, d=64, n_blocks=4, block_size=1024, top_e=2, top_k=1500, dtype=dtype, seed=211)   # C = 2048 = 256 * 8
+    _case(P, T=21, d=64, n_blocks=5, block_size=700, top_e=3, top_k=2049, dtype=dtype, seed=212)    # C = 2100
+
+
+def test_tokens_whose_scores_are_all_equal(P):
+    """Zero rows of h give all-zero scores: every digit of every key is the same (the histogram passes see one bin),
+    the first top_k candidates are selected and contribute nothing."""
+    cfg = synth.small_case(T=48, d=64, n_blocks=6, block_size=64, top_e=2, top_k=30, dtype="bf16", seed=213)
+    t = synth.make_inputs(cfg)
+    t.h[::3] = 0.0
+    from oracle import oracle
+    g = P.run_gpu(t)
+    r = oracle.route(t.h, t.Wg, cfg.top_e, t.bias)
+    f = oracle.forward(t.h, t.K, t.V, r.block_idx, cfg.block_size, cfg.top_k, want_candidates=True)
+    b = oracle.backward(t.h, t.K, t.V, f.idx, f.score, t.dOut, cfg.block_size)
+    rep = P.compare(t, g, r, f, b)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
+    assert (g["idx"][::3] == np.sort(f.idx, 1)[::3]).all()
+    assert (g["act"][::3] == 0).all() and (g["out"][::3] == 0).all()
+
+
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 72)])
 def test_keys_and_values_in_pinned_host_memory(P, dtype, d):
     """MEFT_FLAG_HOST_KV: K, V are read from, and the touched rows of dK, dV written to, pinned host memory.
