@@ -56,7 +56,7 @@ STAGE_SYMBOL = {
     "router_gemm": "gemm_mfma_kernel<ProbRouter, true>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<0>, true>",
     "dact_gemm": "gemm_mfma_kernel<ProbTokKC<1>, true>", "value_gemm": "gemm_mfma_kernel<ProbTokNC, true>",
     "dh_gemm": "gemm_mfma_kernel<ProbTokNC, true>", "dV_gemm": "gemm_mfma_kernel<ProbNeuTN, true>",
-    "dK_gemm": "gemm_mfma_kernel<ProbNeuTN, true>", "topk_select": "topk_select_reg_kernel<16>", "reduce_parts": "reduce_parts_kernel<2>",
+    "dK_gemm": "gemm_mfma_kernel<ProbNeuTN, true>", "topk_select": "topk_select_reg_kernel<16, true>", "reduce_parts": "reduce_parts_kernel<2>",
 }
 
 
