@@ -164,10 +164,13 @@ __global__ __launch_bounds__(1024) void fill_groups_kernel(const int32_t* __rest
 // ---------------------------------------------------------------------------------------------
 constexpr int kTopkEmitLds = 1024;   // selections per token that go through LDS in one round
 
-// Seven waves per SIMD (72 registers): measured best at 16 keys per thread (0.095 ms against 0.102 with the 86
-// registers the compiler takes unasked, 0.118 at six waves, 0.123 at eight)
+// Waves per SIMD that the register allocation aims at.  Up to 16 keys per thread seven (72 registers): measured
+// best at 16 keys (0.095 ms against 0.102 with the 86 registers the compiler takes unasked, 0.118 at six waves, 0.123
+// at eight); with more keys per thread as many as hold them without spilling.
+constexpr int topk_waves(int kpt) { return kpt <= 16 ? 7 : (kpt <= 32 ? 4 : 2); }
+
 template <int KPT, bool kFull>   // kFull: C == 256 * KPT, every position holds a candidate
-__global__ __launch_bounds__(256, 7) void topk_select_reg_kernel(const float* __restrict__ sc,
+__global__ __launch_bounds__(256, topk_waves(KPT)) void topk_select_reg_kernel(const float* __restrict__ sc,
                                                               const int32_t* __restrict__ sblk, int C, int bs,
                                                               int e, int k, int32_t* __restrict__ idx,
                                                               float* __restrict__ act,
