@@ -46,28 +46,59 @@ __global__ void pair_count_kernel(const int32_t* __restrict__ idx, int P, int N,
   if (p < P) atomicAdd(&cnt[clampi(idx[p], 0, N - 1)], 1);
 }
 
-// seg_off = exclusive scan of cnt; touched = ascending ids with cnt > 0.  One workgroup of 1024.
+// seg_off = exclusive scan of cnt; touched = ascending ids with cnt > 0.  One workgroup of 1024; thread t owns a
+// run of consecutive counters (a multiple of 4, so that its 16-byte loads and stores are aligned) and reads them
+// sixteen at a time with independent loads: read one by one, each counter costs a trip to memory.
 __global__ __launch_bounds__(1024) void pair_scan_kernel(const int32_t* __restrict__ cnt, int N,
                                                          int32_t* __restrict__ seg_off,
                                                          int32_t* __restrict__ touched,
                                                          int32_t* __restrict__ n_touched) {
   __shared__ int s_c[16], s_f[16];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int chunk = (N + 1023) / 1024;
+  const int chunk = ((N + 1023) / 1024 + 3) & ~3;
   const int j0 = min(N, tid * chunk), j1 = min(N, j0 + chunk);
+  auto load16 = [&](int j, int (&v)[16]) {
+    if (j + 16 <= j1) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const i32x4 x = *reinterpret_cast<const i32x4*>(cnt + j + 4 * q);
+        v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) v[q] = j + q < j1 ? cnt[j + q] : 0;
+    }
+  };
   int c = 0, f = 0;
-  for (int j = j0; j < j1; ++j) { const int v = cnt[j]; c += v; f += v > 0; }
+  for (int j = j0; j < j1; j += 16) {
+    int v[16];
+    load16(j, v);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { c += v[q]; f += v[q] > 0; }
+  }
   const int ci = wave_incl_scan(c), fi = wave_incl_scan(f);
   if (lane == 63) { s_c[w] = ci; s_f[w] = fi; }
   __syncthreads();
   int cb = 0, fb = 0;
   for (int i = 0; i < w; ++i) { cb += s_c[i]; fb += s_f[i]; }
   int off = cb + ci - c, nt = fb + fi - f;
-  for (int j = j0; j < j1; ++j) {
-    const int v = cnt[j];
-    seg_off[j] = off;
-    off += v;
-    if (v > 0) touched[nt++] = j;
+  for (int j = j0; j < j1; j += 16) {
+    int v[16], o[16];
+    load16(j, v);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { o[q] = off; off += v[q]; }
+    if (j + 16 <= j1) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<i32x4*>(seg_off + j + 4 * q) = i32x4{o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]};
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        if (j + q < j1) seg_off[j + q] = o[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      if (v[q] > 0) touched[nt++] = j + q;   // (v[q] is 0 beyond the run)
   }
   if (tid == 1023) { seg_off[N] = off; *n_touched = nt; }
 }
