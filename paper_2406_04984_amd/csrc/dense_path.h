@@ -211,7 +211,16 @@ struct ProbNeuTN {
   __device__ bool locate(int wg, TileCoord& tc) const {
     const int tm = (bs + kTM - 1) / kTM, tn = (d + kTN - 1) / kTN;
     const int x = wg & (kXcd - 1), local = wg >> 3;
-    const int gi = local / (tm * tn), w = local - gi * (tm * tn);
+    int gi, w;
+    if (as_const(sched.len)[kXcd] != 0) {   // split lists: this XCD takes the tiles x, x + 8, ... of every group
+      const int mine = tm * tn > x ? (tm * tn - x + kXcd - 1) / kXcd : 0;
+      if (mine == 0) return false;
+      gi = local / mine;
+      w = x + kXcd * (local - gi * mine);
+    } else {
+      gi = local / (tm * tn);
+      w = local - gi * (tm * tn);
+    }
     if (gi >= as_const(sched.len)[x]) return false;
     tc.g = as_const(sched.grp)[(size_t)x * sched.cap + gi].x;
     tc.slot0 = as_const(group_off)[tc.g];

@@ -685,7 +685,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 // lengths of the neuron-major problems.  Which XCD computes a group has no influence on any result.
 struct TokenSched {
   const int2* grp;       // [kXcd][cap]
-  const int* len;        // [kXcd] number of groups in the list
+  const int* len;        // [kXcd] number of groups in the list; [kXcd]: 1 = every list holds every group (split)
   int cap;               // entries per XCD (n_groups + 1)
   int max_tiles;         // upper bound of m tiles of one XCD (for the tile-id bound of a launch)
 };
@@ -713,6 +713,10 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
       s_sorted[rank] = rows;
     }
     __syncthreads();
+    // Fewer non-empty groups than XCDs: a deal of whole groups would leave XCDs idle.  Then every list holds every
+    // group, len[kXcd] says so, and XCD x takes the tiles x, x + 8, ... of each group (locate_token_tile).
+    const bool split = n_full < kXcd;
+    if (tid == 0) len[kXcd] = split ? 1 : 0;
     if (tid < 64) {
       // the deal itself is sequential; lanes 0..7 of the first wave each keep one XCD's work, list length and tile
       // count, and a three-step DPP butterfly finds the least loaded XCD (ties to the lower one)
@@ -720,6 +724,14 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
       int load = 0, n = 0, tiles = 0;
       for (int i = 0; i < n_full; ++i) {   // descending order: the non-empty groups come first
         const int g = s_order[i], r = s_sorted[i];
+        if (split) {
+          if (lane < kXcd) {
+            grp[(size_t)lane * cap + n] = make_int2(g, tiles);
+            n += 1;
+            tiles += (r + kTM - 1) / kTM;
+          }
+          continue;
+        }
         int key = lane < kXcd ? ((load << 3) | lane) : 0x7FFFFFFF;
         key = min(key, __builtin_amdgcn_update_dpp(key, key, 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
         key = min(key, __builtin_amdgcn_update_dpp(key, key, 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
@@ -738,6 +750,7 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
     }
   } else if (tid < kXcd) {
     const int x = tid;
+    if (x == 0) len[kXcd] = 0;
     int n = 0, tiles = 0;
     for (int g = x; g < n_groups; g += kXcd) {
       const int rows = group_off[g + 1] - group_off[g];
@@ -760,6 +773,25 @@ __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int
   const int x = wg & (kXcd - 1), local = wg >> 3;
   const int n = as_const(s.len)[x];
   const auto* list = as_const(s.grp) + (size_t)x * s.cap;
+  if (as_const(s.len)[kXcd] != 0) {
+    // split lists (fewer than 8 entries): XCD x takes the tiles x, x + 8, ... of every group, m tiles fastest
+    int rest = local;
+    for (int i = 0; i < n; ++i) {
+      const int tm = list[i + 1].y - list[i].y, all = tm * tn;
+      const int mine = all > x ? (all - x + kXcd - 1) / kXcd : 0;
+      if (rest < mine) {
+        const int w = x + kXcd * rest;
+        g = list[i].x;
+        nt = w / tm;
+        mt = w - nt * tm;
+        slot0 = as_const(group_off)[g];
+        rows = as_const(group_off)[g + 1] - slot0;
+        return true;
+      }
+      rest -= mine;
+    }
+    return false;
+  }
   if (local >= list[n].y * tn) return false;
   int lo = 0, hi = n;  // list[lo].y * tn <= local < list[hi].y * tn
   while (hi - lo > 1) {
