@@ -98,6 +98,12 @@ struct Carver {
 // The matrix-core formulation (dense_path.h) is used for bf16 when the hidden size fits its k tiling and
 // the selection is dense enough inside the chosen blocks; otherwise, and for fp32, the per-pair gather
 // kernels are used.
+// The score contraction alone runs on the matrix-core kernel of the block-dense path also for bf16 shapes that
+// are not dense enough for the rest of it, when the groups are large enough to fill its 128-row tiles.
+bool use_mfma_scores(const meft_shape& s) {
+  return s.dtype == MEFT_BF16 && s.d % kTK == 0 && (int64_t)s.T * s.top_e >= (int64_t)kTM * s.n_blocks;
+}
+
 bool use_dense(const meft_shape& s) {
   const int64_t C = (int64_t)s.top_e * s.block_size;
   return s.dtype == MEFT_BF16 && s.d % kTK == 0 && s.block_size >= 16 && (int64_t)s.top_k * 64 >= C &&
@@ -461,7 +467,7 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
 }
 
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
-void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, hipStream_t st) {
+void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, bool want_sched, hipStream_t st) {
   const int n_ent = s.T * s.top_e;
   if (fast_dispatch(s)) {
     const int n_chunks = (n_ent + 1023) / 1024;
@@ -469,7 +475,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
     MEFT_LAUNCH("dispatch_count", dispatch_count_kernel, dim3(n_chunks), dim3(1024), lds, st, w.sblk, n_ent,
                 s.n_blocks, w.chunk_hist);
     MEFT_LAUNCH("dispatch_scan", dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, w.chunk_hist, n_chunks,
-                s.n_blocks, BM, w.cnt, w.group_off, w.tile_off, sched_cap(s), dense ? w.sched_pairs : nullptr,
+                s.n_blocks, BM, w.cnt, w.group_off, w.tile_off, sched_cap(s), want_sched ? w.sched_pairs : nullptr,
                 w.sched_len);
     MEFT_LAUNCH("dispatch_place", dispatch_place_kernel, dim3(n_chunks), dim3(1024), lds, st, w.sblk, n_ent,
                 s.n_blocks, s.top_e, w.chunk_hist, w.group_off, w.perm, dense ? w.tok_of_slot : nullptr,
@@ -482,6 +488,8 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
   if (dense) {
     MEFT_LAUNCH("slot_maps", slot_maps_kernel, dim3((n_ent + kSlotPad + 255) / 256), dim3(256), 0, st, w.perm, w.group_off,
                 s.n_blocks, s.top_e, w.tok_of_slot, w.slot_of_ent);
+  }
+  if (want_sched) {
     MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks,
                 sched_cap(s), w.sched_pairs, w.sched_len);
   }
@@ -513,13 +521,14 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
   const bool dense = use_dense(s);
   MEFT_LAUNCH("sort_blocks", sort_blocks_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, block_idx, s.T,
               s.top_e, s.n_blocks, w.sblk);
-  launch_dispatch(s, w, BM, dense, st);
+  const bool mfma_scores = dense || use_mfma_scores(s);
+  launch_dispatch(s, w, BM, dense, mfma_scores, st);
   const int bsp = round64(s.block_size);
   const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
   const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
                  *vv = static_cast<const uint16_t*>(V);
   if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
-  if (dense) {
+  if (mfma_scores) {
     ProbTokKC<kTokScores> ps{};
     ps.X = hh; ps.W = kk; ps.perm = w.perm; ps.group_off = w.group_off; ps.sched = sched;
     ps.e = s.top_e; ps.bs = s.block_size; ps.bsp = bsp; ps.d = s.d; ps.sc = w.sc;
@@ -589,7 +598,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
                    *vv = static_cast<const uint16_t*>(V), *gg = static_cast<const uint16_t*>(dOut);
     MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
                 st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
-    launch_dispatch(s, w, kGemmBM, true, st);
+    launch_dispatch(s, w, kGemmBM, true, true, st);
     // the flags and the row of zeros start from zero (adjacent in the workspace); 4-byte fill
     const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.Ap) - reinterpret_cast<char*>(w.flag)) / 4;
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,

@@ -96,6 +96,14 @@ def test_degenerate_selections(P, dtype):
     _case(P, T=40, d=8, n_blocks=48, block_size=1, top_e=6, top_k=6, dtype=dtype, seed=206)     # one neuron per expert
 
 
+def test_matrix_core_scores_on_the_gather_path(P):
+    """bf16 shapes too sparse for the block-dense kernels (64 top_k < candidates) still score on the matrix-core
+    kernel when the hidden size is a multiple of 64 and the groups are large; everything after the scores is the
+    per-pair path.  One and three groups: fewer groups than XCDs, so every XCD takes every eighth tile."""
+    _case(P, T=600, d=128, n_blocks=1, block_size=9000, top_e=1, top_k=20, dtype="bf16", seed=221)
+    _case(P, T=700, d=192, n_blocks=3, block_size=3000, top_e=2, top_k=33, dtype="bf16", seed=222)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_selection_larger_than_one_output_staging_round(P, dtype):
     """top_k beyond the 1024 selections that the selection kernel stages per round, candidate counts on and off the
