@@ -91,7 +91,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="llama7b_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--verify", action="store_true", help="check structural invariants of one step first")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements beside the headline metric (optimizer step, batch-union variant); "
