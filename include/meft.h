@@ -268,6 +268,16 @@ meft_status meft_adam_rows(const meft_shape* shape, const meft_adam* hp, void* W
  */
 meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/*
+ * Measurement aid (not part of the paper's method): a loop of bf16 matrix instructions and nothing else, as one
+ * kernel on `stream`: `workgroups` workgroups of four waves, each wave issuing 8 * iters instructions
+ * v_mfma_f32_32x32x16_bf16 (32768 flop each) on pseudo-random finite operands.  The rate it reaches is what the
+ * matrix cores of this machine sustain, to set beside the published peak.  `out`: device memory for
+ * workgroups * 256 floats (written, content of no interest).  It appears in meft_profile_read as "probe_mfma".
+ * Errors: MEFT_ERR_INVALID_ARG (null pointer, workgroups outside 1..65536, iters < 1), MEFT_ERR_DEVICE.
+ */
+meft_status meft_probe_mfma(float* out, int workgroups, int iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

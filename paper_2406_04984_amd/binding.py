@@ -21,7 +21,7 @@ MEFT_FLAG_PRESTAGED = 4
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
-           "meft_probe_copy", "meft_adam_rows", "meft_last_device_error",
+           "meft_probe_copy", "meft_probe_mfma", "meft_adam_rows", "meft_last_device_error",
            "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd", "meft_hostkv_stage")
 
 
@@ -82,6 +82,8 @@ _lib.meft_last_device_error.restype = ctypes.c_char_p
 _lib.meft_last_device_error.argtypes = []
 _lib.meft_probe_copy.restype = ctypes.c_int
 _lib.meft_probe_copy.argtypes = [_vp, _vp, _sz, _vp]
+_lib.meft_probe_mfma.restype = ctypes.c_int
+_lib.meft_probe_mfma.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp]
 _lib.meft_profile_enable.restype = None
 _lib.meft_profile_enable.argtypes = [ctypes.c_int]
 _lib.meft_profile_read.restype = ctypes.c_int
@@ -203,6 +205,13 @@ def meft_probe_copy(dst, src, nbytes: int, stream=None, check=True) -> int:
     rc = _lib.meft_probe_copy(_p(dst), _p(src), nbytes, _stream(stream))
     if check and rc:
         raise MeftError("meft_probe_copy", rc)
+    return rc
+
+
+def meft_probe_mfma(out, workgroups: int, iters: int, stream=None, check=True) -> int:
+    rc = _lib.meft_probe_mfma(_p(out), workgroups, iters, _stream(stream))
+    if check and rc:
+        raise MeftError("meft_probe_mfma", rc)
     return rc
 
 

@@ -990,6 +990,14 @@ meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stre
   return launch_status();
 }
 
+meft_status meft_probe_mfma(float* out, int workgroups, int iters, void* stream) {
+  if (!out || workgroups < 1 || workgroups > 65536 || iters < 1) return MEFT_ERR_INVALID_ARG;
+  clear_stale_error();
+  MEFT_LAUNCH("probe_mfma", probe_mfma_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), out,
+              iters);
+  return launch_status();
+}
+
 const char* meft_last_device_error(void) { return hipGetErrorString(g_last_device_error); }
 
 void meft_profile_enable(int on) {

@@ -20,6 +20,45 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4* __restrict__ dst
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+// A loop of nothing but matrix instructions: every wave keeps eight independent 32 x 32 accumulators busy with
+// v_mfma_f32_32x32x16_bf16 on operands of pseudo-random bits (finite bf16 values; what a matrix core draws depends on
+// how many bits toggle).  Gives the rate the matrix cores sustain on this machine: the published peak assumes a
+// clock that a chip under this load does not hold.  Each thread stores one float so that the loop is not removed.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ out, int iters) {
+  const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
+  uint32_t x = tid * 2654435761u + 12345u;
+  auto next = [&]() {   // two bf16 values with exponents 0x3F/0x40: magnitudes between 0.5 and 4, random signs
+    x = x * 1664525u + 1013904223u;
+    return (x & 0x80FF80FFu) | 0x3F003F00u;
+  };
+  bf16x8 a[2], b[4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) a[i] = __builtin_bit_cast(bf16x8, u32x4{next(), next(), next(), next()});
+#pragma unroll
+  for (int j = 0; j < 4; ++j) b[j] = __builtin_bit_cast(bf16x8, u32x4{next(), next(), next(), next()});
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+  out[tid] = sum;
+}
+
 // block id of every (token, neuron) pair (ids clamped into range)
 __global__ void blocks_of_pairs_kernel(const int32_t* __restrict__ idx, int P, int N, int bs,
                                        int32_t* __restrict__ blk) {

@@ -143,3 +143,14 @@ def test_union_calls_validate_on_the_host(B):
     f32 = _shape(B, dtype="f32")
     assert B.meft_union_workspace_bytes(f32) == 0
     assert f(ctypes.byref(f32), fake, fake, fake, fake, fake, fake, fake, fake, 1 << 30, None) == B.MEFT_ERR_UNSUPPORTED
+
+
+def test_probes_validate_on_the_host(B):
+    fake = 0x1000
+    assert B._lib.meft_probe_copy(None, fake, 16, None) == B.MEFT_ERR_INVALID_ARG
+    assert B._lib.meft_probe_copy(fake, fake + 8, 16, None) == B.MEFT_ERR_INVALID_ARG
+    assert B._lib.meft_probe_copy(fake, fake, 24, None) == B.MEFT_ERR_INVALID_ARG
+    assert B._lib.meft_probe_mfma(None, 4, 4, None) == B.MEFT_ERR_INVALID_ARG
+    assert B._lib.meft_probe_mfma(fake, 0, 4, None) == B.MEFT_ERR_INVALID_ARG
+    assert B._lib.meft_probe_mfma(fake, 65537, 4, None) == B.MEFT_ERR_INVALID_ARG
+    assert B._lib.meft_probe_mfma(fake, 4, 0, None) == B.MEFT_ERR_INVALID_ARG

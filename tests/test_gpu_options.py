@@ -102,3 +102,17 @@ def test_global_load_kernels_match_the_buffer_load_kernels(monkeypatch):
     ref = P.run_gpu(t)
     monkeypatch.setenv("MEFT_GLOBAL_LOADS", "1")
     _same(ref, P.run_gpu(t))
+
+
+def test_measurement_probes_run():
+    """The streaming-copy probe copies; the matrix-instruction probe fills its output with finite sums."""
+    import torch
+    from paper_2406_04984_amd import binding as B
+    a = torch.arange(1 << 16, dtype=torch.int32, device="cuda")
+    b = torch.zeros_like(a)
+    B.meft_probe_copy(b, a, a.numel() * 4)
+    out = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    B.meft_probe_mfma(out, 8, 16)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert bool(torch.isfinite(out).all()) and bool((out != 0).any())
