@@ -338,6 +338,8 @@ def main() -> int:
                    "inputs_resident_in_hbm": True, "input_generation_s": round(gen_s, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stages,
         "measured_copy_GB/s": round(copy_gbs, 1), "measured_mfma_TFLOP/s": round(mfma_tflops, 1),
+        # 256 compute units x 4 matrix cores x 1024 flop per clock (a 32x32x16 bf16 instruction takes 32 clocks)
+        "matrix_clock_GHz_implied_by_probe": round(mfma_tflops * 1e12 / (256 * 4 * 1024) / 1e9, 2),
         "beyond_the_metric": extra,
     }
     print(json.dumps(line))
