@@ -161,7 +161,7 @@ def main() -> int:
     copy_gbs = 2.0 * probe_bytes / (copy_ms * 1e-3) / 1e9
     del pa, pb
 
-    # matrix-instruction probe: 1024 workgroups x 4 waves x 8 * 4096 instructions of 32768 flop (about 0.8 ms)
+    # matrix-instruction probe: 1024 workgroups x 4 waves x 8 * 4096 instructions of 32768 flop (about 2.4 ms)
     probe_wgs, probe_iters = 1024, 4096
     pm = torch.empty((probe_wgs * 256,), dtype=torch.float32, device="cuda")
     for _ in range(2):
