@@ -35,8 +35,22 @@
  *  - Arguments are validated on the host before anything is enqueued; a non-zero status means
  *    nothing was enqueued.  Faults that happen on the device later surface at the caller's next
  *    synchronisation.  Inputs must be finite (the ordering of NaN is unspecified).
- *  - dtype applies to h, Wg, K, V, out, dOut, dh, dK, dV.  Accumulation is fp32; results are rounded
- *    once (to nearest even) when stored.
+ *  - dtype applies to h, Wg, K, V, out, dOut, dh, dK, dV.  Every sum is accumulated in fp32 and a result is
+ *    rounded (to nearest even) when it is stored.  With MEFT_F32, and for bf16 shapes that run on the per-pair
+ *    kernels (see "Precision" below), that is the only rounding.  bf16 shapes that run on the matrix cores round at
+ *    these further points, each to bf16, nearest even:
+ *      - the activation max(score, 0) when it enters a contraction as an operand (the value sum of Eq. 4 and dV);
+ *        `act` itself is returned in fp32, unrounded;
+ *      - the masked activation gradient ds when it enters a contraction as an operand (dh and dK);
+ *      - a token's output row and input-gradient row are each the sum of top_e per-block partial rows; a partial
+ *        row is rounded to bf16 when stored, the partial rows are summed in fp32 (blocks in ascending id) and
+ *        the sum is rounded again.  out and dh therefore see three roundings (operand, partial row, result),
+ *        dK and dV two (operand, result); each rounding has relative size at most 2^-9.
+ *    Precision: a bf16 shape runs on the matrix cores when d is a multiple of 64, block_size >= 16,
+ *    64 * top_k >= top_e * block_size and top_e * block_size <= 12288; otherwise on the per-pair kernels.
+ *  - Host threads: the entry points may be called from several host threads; their host side (validation, launches,
+ *    the library's few pieces of process-wide state) is serialised by a lock inside the library.  Ordering of the
+ *    enqueued work is the caller's, through the streams.
  */
 #ifndef MEFT_H
 #define MEFT_H
@@ -220,6 +234,14 @@ meft_status meft_union_fwd(const meft_shape* shape, const void* h, const void* K
 meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K, const void* V, const int32_t* S,
                            const int32_t* n_S, const void* dOut, void* dh, void* dK, void* dV, void* ws,
                            size_t ws_bytes, void* stream);
+
+/*
+ * Test aid (not part of the paper's method): the matrix-core kernels read operand matrices below 4 GB through
+ * buffer resources and larger ones through 64-bit global pointers.  on != 0 selects the global-pointer kernels at
+ * any size, so that a test reaches them with small inputs; on == 0 restores the choice by size.  The initial state
+ * is that of the environment variable MEFT_GLOBAL_LOADS ("1" = on), read once when the library is loaded.
+ */
+void meft_debug_global_loads(int on);
 
 /*
  * Diagnostics: the runtime's description of the launch failure behind the calling thread's most recent

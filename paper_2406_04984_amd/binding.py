@@ -22,7 +22,8 @@ MEFT_FLAG_PRESTAGED = 4
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
            "meft_probe_copy", "meft_probe_mfma", "meft_adam_rows", "meft_last_device_error",
-           "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd", "meft_hostkv_stage")
+           "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd", "meft_hostkv_stage",
+           "meft_debug_global_loads")
 
 
 class MeftShape(ctypes.Structure):
@@ -86,6 +87,8 @@ _lib.meft_probe_mfma.restype = ctypes.c_int
 _lib.meft_probe_mfma.argtypes = [_vp, ctypes.c_int, ctypes.c_int, _vp]
 _lib.meft_profile_enable.restype = None
 _lib.meft_profile_enable.argtypes = [ctypes.c_int]
+_lib.meft_debug_global_loads.restype = None
+_lib.meft_debug_global_loads.argtypes = [ctypes.c_int]
 _lib.meft_profile_read.restype = ctypes.c_int
 _lib.meft_profile_read.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_i32),
                                    ctypes.POINTER(ctypes.c_float), ctypes.c_int]
@@ -213,6 +216,10 @@ def meft_probe_mfma(out, workgroups: int, iters: int, stream=None, check=True) -
     if check and rc:
         raise MeftError("meft_probe_mfma", rc)
     return rc
+
+
+def meft_debug_global_loads(on: bool) -> None:
+    _lib.meft_debug_global_loads(1 if on else 0)
 
 
 def meft_profile_enable(on: bool) -> None:

@@ -3,10 +3,12 @@
 // the kernels of the headers included below.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -23,6 +25,12 @@
 
 namespace meft {
 namespace {
+
+// The host side of every entry point that enqueues work or touches the library's few pieces of process-wide state
+// (the timing list, the side stream and events of the host-resident variant, the table of staged workspaces) runs
+// under this lock, so the entry points may be called from several host threads.
+std::mutex g_api_mutex;
+#define MEFT_API_LOCK() std::lock_guard<std::mutex> api_lock_(g_api_mutex)
 
 // ---- per-kernel timing ----------------------------------------------------------------------
 struct ProfEntry {
@@ -153,7 +161,7 @@ struct DispatchWs {
     perm = c.take<int32_t>(n_ent);
     tok_of_slot = c.take<int32_t>(n_ent + kSlotPad);   // padded: see kSlotPad
     slot_of_ent = c.take<int32_t>(n_ent);
-    sched_len = c.take<int32_t>(kXcd);
+    sched_len = c.take<int32_t>(kXcd + 1);   // one list length per XCD, then the split flag
     sched_pairs = c.take<int2>((size_t)kXcd * sched_cap(s));
     chunk_hist = c.take<int32_t>(fast_dispatch(s) ? ((n_ent + 1023) / 1024) * (size_t)s.n_blocks : 0);
   }
@@ -436,11 +444,16 @@ constexpr int kPersistentWgs = 256;   // compute units of an MI355X; a multiple 
 // Bytes readable from an operand's lowest address; buffer loads (32-bit offsets) where both fit.  Setting
 // MEFT_GLOBAL_LOADS=1 in the environment selects the global-load kernels (those for operands of 4 GB and more)
 // at any size, so that tests reach them with small inputs.
+// (the environment is read once, when the library is loaded; meft_debug_global_loads overrides it)
+std::atomic<int> g_force_global_loads{[] {
+  const char* env = getenv("MEFT_GLOBAL_LOADS");
+  return (env && env[0] == '1') ? 1 : 0;
+}()};
+
 template <class P>
 void set_gemm_extents(P& p, uint64_t a_bytes, uint64_t b_bytes) {
   constexpr uint64_t kLimit = 0xFFFF0000ull;
-  const char* env = getenv("MEFT_GLOBAL_LOADS");
-  const bool forced_global = env && env[0] == '1';
+  const bool forced_global = g_force_global_loads.load(std::memory_order_relaxed) != 0;
   p.buf = !forced_global && a_bytes < kLimit && b_bytes < kLimit;
   p.a_bytes = p.buf ? (uint32_t)a_bytes : 0u;
   p.b_bytes = p.buf ? (uint32_t)b_bytes : 0u;
@@ -448,14 +461,13 @@ void set_gemm_extents(P& p, uint64_t a_bytes, uint64_t b_bytes) {
 
 template <class P>
 void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st) {
-  static bool configured = false;  // raise the dynamic LDS limit of both instantiations once
-  if (!configured) {
+  static std::once_flag configured;  // raise the dynamic LDS limit of both instantiations once
+  std::call_once(configured, [] {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P, false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P, true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
-    configured = true;
-  }
+  });
   // persistent workgroups: one per compute unit (the LDS footprint allows no more), each walking the tile ids
   // wg, wg + 256, ... below `grid`
   const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
@@ -508,6 +520,30 @@ void launch_reduce_parts(const meft_shape& s, const uint16_t* part, const Dispat
 }  // namespace meft
 
 using namespace meft;
+
+// Router scores (as up to kRouterSplitMax partial sums over slices of the hidden dimension, in `p`) and the top-e
+// selection over their sum.
+static meft_status route_impl(const meft_shape& s, const void* h, const void* Wg, const float* bias,
+                              int32_t* block_idx, float* block_score, float* p, hipStream_t st) {
+  int n_part = 1;
+  if (s.dtype == MEFT_BF16 && s.d % kTK == 0) {
+    const int kt = s.d / kTK;
+    n_part = kt % 4 == 0 ? 4 : (kt % 2 == 0 ? 2 : 1);
+    ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), p, s.T, s.d, s.n_blocks, n_part};
+    set_gemm_extents(pr, (uint64_t)s.T * s.d * 2, (uint64_t)s.n_blocks * s.d * 2);
+    launch_gemm_mfma("router_gemm", pr, n_part * ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
+  } else {
+    GemmNTArgs a{};
+    a.A = h; a.Bm = Wg; a.C = p; a.perm = nullptr; a.group_off = nullptr; a.tile_off = nullptr;
+    a.n_groups = 1; a.M = s.T; a.Ng = s.n_blocks; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d; a.ldc = s.n_blocks;
+    a.e = 1;
+    launch_gemm_nt(s, a, (s.T + kGemmBM - 1) / kGemmBM, (s.T + kGemmF32BM - 1) / kGemmF32BM, "router_gemm", st);
+  }
+  MEFT_LAUNCH("route_topk", route_topk_kernel, dim3(s.T), dim3(64), (size_t)s.n_blocks * 4, st, p, n_part,
+              (size_t)s.T * s.n_blocks, bias,
+              s.n_blocks, s.top_e, block_idx, block_score);
+  return launch_status();
+}
 
 // Forward on device-resident K, V.  wait_k / wait_v (may be null): events the stream must wait for before
 // the first kernel that reads K / V (used when they are being staged from host memory).
@@ -603,6 +639,13 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.Ap) - reinterpret_cast<char*>(w.flag)) / 4;
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
                 clear_words, 0);
+    // a token's rows take top_e * bsp * 2 bytes of LDS: up to 96 KB where blocks are small and many (the default
+    // limit of a launch is 64 KB)
+    static std::once_flag act_rows_configured;
+    std::call_once(act_rows_configured, [] {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&act_rows_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kMaxLdsC * 2);
+    });
     MEFT_LAUNCH("act_rows", act_rows_kernel, dim3(s.T), dim3(256), (size_t)s.top_e * bsp * 2, st, idx, act, s.top_k,
                 s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.Ap, w.flag);
     const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
@@ -710,6 +753,7 @@ meft_status meft_union_fwd(const meft_shape* shape, const void* h, const void* K
   const UnionWs w(s, g, ws);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return MEFT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
   if (s.T == 0) {
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3(1), dim3(64), 0, st, n_S, (size_t)1, 0);
@@ -751,6 +795,7 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return MEFT_ERR_WORKSPACE;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
   union_front(s, g, w, h, K, V, S, n_S, st);
   const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(g.vs), sched_max_tiles(g.vs)};
@@ -814,26 +859,9 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
-  int n_part = 1;
-
-  if (s.dtype == MEFT_BF16 && s.d % kTK == 0) {
-    const int kt = s.d / kTK;
-    n_part = kt % 4 == 0 ? 4 : (kt % 2 == 0 ? 2 : 1);
-    ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), w.p, s.T, s.d, s.n_blocks, n_part};
-    set_gemm_extents(pr, (uint64_t)s.T * s.d * 2, (uint64_t)s.n_blocks * s.d * 2);
-    launch_gemm_mfma("router_gemm", pr, n_part * ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
-  } else {
-    GemmNTArgs a{};
-    a.A = h; a.Bm = Wg; a.C = w.p; a.perm = nullptr; a.group_off = nullptr; a.tile_off = nullptr;
-    a.n_groups = 1; a.M = s.T; a.Ng = s.n_blocks; a.Kdim = s.d; a.lda = s.d; a.ldb = s.d; a.ldc = s.n_blocks;
-    a.e = 1;
-    launch_gemm_nt(s, a, (s.T + kGemmBM - 1) / kGemmBM, (s.T + kGemmF32BM - 1) / kGemmF32BM, "router_gemm", st);
-  }
-  MEFT_LAUNCH("route_topk", route_topk_kernel, dim3(s.T), dim3(64), (size_t)s.n_blocks * 4, st, w.p, n_part,
-              (size_t)s.T * s.n_blocks, bias,
-              s.n_blocks, s.top_e, block_idx, block_score);
-  return launch_status();
+  return route_impl(s, h, Wg, bias, block_idx, block_score, w.p, st);
 }
 
 meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* K, const void* V,
@@ -848,6 +876,7 @@ meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* 
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
   if (!(s.flags & MEFT_FLAG_HOST_KV)) return fwd_impl(s, h, K, V, block_idx, out, idx, act, w, st, nullptr, nullptr);
 
@@ -880,6 +909,7 @@ meft_status meft_hostkv_stage(const meft_shape* shape, const int32_t* block_idx,
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   if (s.T == 0) return MEFT_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
   if (!hostkv_init()) return MEFT_ERR_DEVICE;
   HostKvWs hw(s, ws);
@@ -908,6 +938,7 @@ meft_status meft_sparse_bwd(const meft_shape* shape, const void* h, const void* 
   BwdWs w(s, ws);
   if ((rc = check_ws(s, ws, ws_bytes)) != MEFT_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
   if (s.T == 0) {
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3(1), dim3(64), 0, st, n_touched, (size_t)1, 0);
@@ -970,6 +1001,7 @@ meft_status meft_adam_rows(const meft_shape* shape, const meft_adam* hp, void* W
   const int64_t cap = (int64_t)s.T * s.top_k < (int64_t)s.N ? (int64_t)s.T * s.top_k : (int64_t)s.N;
   const int grid = (int)(cap < 4096 ? cap : 4096);   // rows are walked with a grid stride
   hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
   clear_stale_error();
   if (s.dtype == MEFT_BF16)
     MEFT_LAUNCH("adam_rows", adam_rows_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, static_cast<bf16_t*>(W),
@@ -984,6 +1016,7 @@ meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stre
   if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0) return MEFT_ERR_INVALID_ARG;
   if (bytes == 0) return MEFT_OK;
   const size_t n = bytes / 16;
+  MEFT_API_LOCK();
   clear_stale_error();
   MEFT_LAUNCH("probe_copy", probe_copy_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
               static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n);
@@ -992,6 +1025,7 @@ meft_status meft_probe_copy(void* dst, const void* src, size_t bytes, void* stre
 
 meft_status meft_probe_mfma(float* out, int workgroups, int iters, void* stream) {
   if (!out || workgroups < 1 || workgroups > 65536 || iters < 1) return MEFT_ERR_INVALID_ARG;
+  MEFT_API_LOCK();
   clear_stale_error();
   MEFT_LAUNCH("probe_mfma", probe_mfma_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), out,
               iters);
@@ -1000,7 +1034,10 @@ meft_status meft_probe_mfma(float* out, int workgroups, int iters, void* stream)
 
 const char* meft_last_device_error(void) { return hipGetErrorString(g_last_device_error); }
 
+void meft_debug_global_loads(int on) { g_force_global_loads.store(on ? 1 : 0, std::memory_order_relaxed); }
+
 void meft_profile_enable(int on) {
+  MEFT_API_LOCK();
   for (auto& e : g_prof) {
     (void)hipEventDestroy(e.start);
     (void)hipEventDestroy(e.stop);
@@ -1010,6 +1047,7 @@ void meft_profile_enable(int on) {
 }
 
 int meft_profile_read(const char** names, int32_t* launches, float* total_ms, int cap) {
+  MEFT_API_LOCK();
   int n = 0;
   for (auto& e : g_prof) {
     if (hipEventSynchronize(e.stop) != hipSuccess) continue;

@@ -6,148 +6,34 @@ Rules
     identical, except that a token may differ where the oracle's own scores tie to within 1e-5
     relative at the selection boundary: every id in the symmetric difference must then have an
     oracle score within 1e-5*|s_b| of s_b, the oracle's last selected score;
-  * tokens whose selection differs inside that band are valid but not unique: they are left out
-    of the value comparisons (out, dh), and the neurons in their symmetric differences are left
-    out of the row comparisons (dK, dV, touched);
-  * out, dh, dK, dV agree within relative L2 2e-2 (bf16) / 1e-4 (fp32) over everything else;
+  * a token whose selection differs inside that band holds a valid selection that is not the
+    oracle's: its values are judged by REPLAY -- the oracle's steps after the selection
+    (activation-weighted value sum, backward) are run on the selection the HIP path took, with
+    the oracle's own fp64 scores for those neurons, and everything is compared against that.
+    Nothing is left out of the value comparison except tokens outside the band (which fail);
+  * out, dh, dK, dV agree within relative L2 2e-2 (bf16) / 1e-4 (fp32) over the whole tensor, AND
+    row by row: |x_r - y_r|_2 <= tol |y_r|_2 + 1e-2 tol rms(y) sqrt(d); a row the oracle has exactly
+    zero must be exactly zero;
   * rows of dK, dV outside `touched` still hold the sentinel they were filled with.
+A selected pair whose oracle score is within 1e-5 (relative to the token's largest score) of the
+ReLU kink may take either branch of the derivative in fp32; its token / neuron rows are left out of
+the row-by-row check (and counted in the report).
 """
 from __future__ import annotations
 
 import dataclasses
-from typing import Dict, List, Optional
+from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
 from oracle import oracle
 from paper_2406_04984_amd import synth
+from paper_2406_04984_amd.harness import (SENTINEL_BF16, SENTINEL_F32, DeviceLayer, to_device,  # noqa: F401
+                                          to_host, to_pinned)
 
 TIE_BAND = 1e-5
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-SENTINEL_BF16 = 0x7FC1      # a NaN pattern no computation produces
-SENTINEL_F32 = 0x7FC00001
-
-
-def _torch():
-    import torch
-    return torch
-
-
-def to_device(t: synth.Tensors, name: str):
-    torch = _torch()
-    a = t.storage(name)
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(a).cuda()
-
-
-def to_pinned(t: synth.Tensors, name: str):
-    torch = _torch()
-    a = t.storage(name)
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).pin_memory()
-    return torch.from_numpy(a).pin_memory()
-
-
-def to_host(x) -> np.ndarray:
-    torch = _torch()
-    if x.dtype == torch.bfloat16:
-        return x.float().cpu().numpy()
-    return x.cpu().numpy()
-
-
-class DeviceLayer:
-    """Device buffers of one layer and the three ABI calls on them."""
-
-    def __init__(self, t: synth.Tensors, binding=None):
-        torch = _torch()
-        if binding is None:
-            from paper_2406_04984_amd import binding
-        self.B = binding
-        c = t.cfg
-        self.cfg = c
-        self.shape = binding.make_shape(c.T, c.d, c.n_blocks, c.block_size, c.top_e, c.top_k, c.dtype,
-                                        flags=(binding.MEFT_FLAG_HOST_KV if c.host_kv else 0) |
-                                              (binding.MEFT_FLAG_KEEP_STAGED if c.host_kv and c.keep_staged else 0))
-        self.dt = torch.bfloat16 if c.dtype == "bf16" else torch.float32
-        dev = "cuda"
-        self.h, self.Wg, self.dOut = (to_device(t, n) for n in ("h", "Wg", "dOut"))
-        if c.host_kv:   # keys and values (and their gradients) stay in pinned host memory
-            self.K, self.V = (to_pinned(t, n) for n in ("K", "V"))
-        else:
-            self.K, self.V = (to_device(t, n) for n in ("K", "V"))
-        self.bias = None if t.bias is None else torch.from_numpy(t.bias).cuda()
-        T, d, N, e, k = c.T, c.d, c.N, c.top_e, c.top_k
-        self.block_idx = torch.full((T, e), -1, dtype=torch.int32, device=dev)
-        self.block_score = torch.zeros((T, e), dtype=torch.float32, device=dev)
-        self.out = torch.zeros((T, d), dtype=self.dt, device=dev)
-        self.idx = torch.full((T, k), -1, dtype=torch.int32, device=dev)
-        self.act = torch.zeros((T, k), dtype=torch.float32, device=dev)
-        self.dh = torch.zeros((T, d), dtype=self.dt, device=dev)
-        if c.host_kv:
-            self.dK = torch.zeros((N, d), dtype=self.dt).pin_memory()
-            self.dV = torch.zeros((N, d), dtype=self.dt).pin_memory()
-        else:
-            self.dK = torch.zeros((N, d), dtype=self.dt, device=dev)
-            self.dV = torch.zeros((N, d), dtype=self.dt, device=dev)
-        self.touched = torch.full((max(1, min(N, T * k)),), -1, dtype=torch.int32, device=dev)
-        self.n_touched = torch.full((1,), -1, dtype=torch.int32, device=dev)
-        nbytes = binding.meft_workspace_bytes(self.shape)
-        assert nbytes > 0, "shape rejected"
-        self.ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
-
-    def fill_grad_sentinel(self):
-        torch = _torch()
-        if self.dt == torch.bfloat16:
-            self.dK.view(torch.int16).fill_(SENTINEL_BF16)
-            self.dV.view(torch.int16).fill_(SENTINEL_BF16)
-        else:
-            self.dK.view(torch.int32).fill_(SENTINEL_F32)
-            self.dV.view(torch.int32).fill_(SENTINEL_F32)
-
-    def route(self):
-        self.B.meft_route(self.shape, self.h, self.Wg, self.bias, self.block_idx, self.block_score, self.ws)
-
-    def fwd(self):
-        self.B.meft_sparse_fwd(self.shape, self.h, self.K, self.V, self.block_idx, self.out, self.idx,
-                               self.act, self.ws)
-
-    def bwd(self, want_dh=True):
-        self.B.meft_sparse_bwd(self.shape, self.h, self.K, self.V, self.idx, self.act, self.dOut,
-                               self.dh if want_dh else None, self.dK, self.dV, self.touched, self.n_touched,
-                               self.ws)
-
-    def step(self):
-        self.route()
-        self.fwd()
-        self.bwd()
-
-    def results(self, rows: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
-        """Copies results to the host.  `rows`: fetch dK / dV only for these neuron ids (large shapes);
-        the sentinel checks over all rows are evaluated on the device either way."""
-        torch = _torch()
-        torch.cuda.synchronize()
-        nt = int(self.n_touched.item())
-        bf = self.dt == torch.bfloat16
-        ibits = torch.int16 if bf else torch.int32
-        sent = SENTINEL_BF16 if bf else SENTINEL_F32
-        sent_signed = sent - (1 << 16) if (bf and sent >= (1 << 15)) else sent
-        r = dict(block_idx=to_host(self.block_idx), block_score=to_host(self.block_score),
-                 out=to_host(self.out), idx=to_host(self.idx), act=to_host(self.act), dh=to_host(self.dh),
-                 touched=to_host(self.touched)[:max(nt, 0)], n_touched=nt)
-        for name, x in (("dK", self.dK), ("dV", self.dV)):
-            is_s = x.view(ibits) == sent_signed
-            r[name + "_row_all_sentinel"] = is_s.all(dim=1).cpu().numpy()
-            r[name + "_row_any_sentinel"] = is_s.any(dim=1).cpu().numpy()
-            del is_s
-            if rows is None:
-                r[name] = to_host(x)
-                r[name + "_bits"] = x.view(ibits).cpu().numpy()
-            else:
-                sel = torch.from_numpy(np.asarray(rows, np.int64)).to(x.device)
-                r[name] = to_host(x.index_select(0, sel))
-        r["grad_rows"] = None if rows is None else np.asarray(rows, np.int64)
-        return r
+ROW_FLOOR = 1e-2        # absolute slack of a row, in units of tol * (rms of the tensor) * sqrt(d)
 
 
 def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
@@ -158,31 +44,73 @@ def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
     return float(num / den) if den > 0 else float(num)
 
 
+def row_check(x: np.ndarray, y: np.ndarray, tol: float, skip: Optional[np.ndarray] = None) -> Tuple[float, int, int]:
+    """Row-by-row bound of x against the oracle's y.  Returns (largest error / bound over the rows,
+    index of that row, number of rows the oracle has exactly zero that are not exactly zero in x)."""
+    x = np.asarray(x, np.float64)
+    y = np.asarray(y, np.float64)
+    if y.size == 0:
+        return 0.0, -1, 0
+    d = y.shape[1]
+    floor = ROW_FLOOR * tol * float(np.sqrt(np.mean(y * y))) * np.sqrt(d)
+    err = np.linalg.norm(x - y, axis=1)
+    bound = tol * np.linalg.norm(y, axis=1) + floor
+    zero = ~y.any(axis=1)
+    nonzero_where_zero = zero & x.any(axis=1)
+    ratio = np.where(bound > 0, err / np.where(bound > 0, bound, 1.0), np.where(err > 0, np.inf, 0.0))
+    if skip is not None:
+        ratio = np.where(skip, 0.0, ratio)
+        nonzero_where_zero &= ~skip
+    w = int(np.argmax(ratio))
+    return float(ratio[w]), w, int(nonzero_where_zero.sum())
+
+
+def stratified_rows(cfg: synth.Config, n_random: int, tile: int = 128) -> np.ndarray:
+    """Neuron rows for a sampled dK / dV comparison: of every block the first and the last neuron and the two
+    rows on either side of every `tile`-row boundary inside it, plus `n_random` seeded random rows."""
+    bs = cfg.block_size
+    inside = {0, bs - 1}
+    for m in range(tile, bs, tile):
+        inside.update((m - 1, m))
+    base = (np.arange(cfg.n_blocks)[:, None] * bs + np.array(sorted(inside))[None, :]).ravel()
+    rnd = np.random.default_rng(cfg.seed).choice(cfg.N, size=min(n_random, cfg.N), replace=False)
+    return np.unique(np.concatenate([base, rnd])).astype(np.int32)
+
+
 @dataclasses.dataclass
 class Report:
     name: str
     dtype: str
     tokens: int
-    block_band_tokens: int = 0          # tokens whose block set differs inside the tie band
+    block_band_tokens: int = 0          # tokens whose block set differs inside the tie band (replayed)
     block_bad_tokens: int = 0           # ... outside the band (failure)
-    idx_band_tokens: int = 0
+    idx_band_tokens: int = 0            # tokens whose neuron set differs inside the tie band (replayed)
     idx_bad_tokens: int = 0
     invariant_errors: List[str] = dataclasses.field(default_factory=list)
-    err: Dict[str, float] = dataclasses.field(default_factory=dict)
-    excluded_rows: int = 0
+    err: Dict[str, float] = dataclasses.field(default_factory=dict)        # whole-tensor relative L2
+    row_err: Dict[str, Tuple[float, int]] = dataclasses.field(default_factory=dict)   # worst row: (err / bound, row)
+    zero_rows_not_zero: Dict[str, int] = dataclasses.field(default_factory=dict)
+    kink_pairs: int = 0
+    rows_compared: int = 0
     n_touched: int = 0
 
     def ok(self) -> bool:
         tol = TOL[self.dtype]
         return (self.block_bad_tokens == 0 and self.idx_bad_tokens == 0 and not self.invariant_errors
                 and all(v <= tol for v in self.err.values())
+                and all(v[0] <= 1.0 for v in self.row_err.values())
+                and all(v == 0 for v in self.zero_rows_not_zero.values())
                 and (self.block_band_tokens + self.idx_band_tokens) <= max(2, 0.05 * self.tokens))
 
     def summary(self) -> str:
         e = " ".join(f"{k}={v:.2e}" for k, v in self.err.items())
+        rw = " ".join(f"{k}:{v[0]:.2f}@{v[1]}" for k, v in self.row_err.items())
+        z = {k: v for k, v in self.zero_rows_not_zero.items() if v}
         return (f"{self.name}: tokens={self.tokens} blocks(band/bad)={self.block_band_tokens}/{self.block_bad_tokens} "
                 f"idx(band/bad)={self.idx_band_tokens}/{self.idx_bad_tokens} touched={self.n_touched} "
-                f"excluded_rows={self.excluded_rows} {e} invariants={self.invariant_errors or 'ok'}")
+                f"grad_rows={self.rows_compared} kink_pairs={self.kink_pairs} {e} "
+                f"worst_row(err/bound@row) {rw} zero_rows_not_zero={z or 0} "
+                f"invariants={self.invariant_errors or 'ok'}")
 
     def assert_ok(self):
         assert self.ok(), self.summary()
@@ -192,16 +120,28 @@ def _band_ok(diff_scores: np.ndarray, boundary: float) -> bool:
     return bool(np.all(np.abs(diff_scores - boundary) <= TIE_BAND * abs(boundary)))
 
 
+def _lookup(cand_id: np.ndarray, cand_score: np.ndarray, ids: np.ndarray):
+    """Oracle scores of `ids` among a token's candidates (ascending ids); second result: all found."""
+    pos = np.searchsorted(cand_id, ids)
+    pos_c = np.minimum(pos, cand_id.size - 1)
+    found = (pos < cand_id.size) & (cand_id[pos_c] == ids)
+    return cand_score[pos_c], bool(found.all())
+
+
 def compare(t: synth.Tensors, g: Dict[str, np.ndarray], r: oracle.Route, f: oracle.Forward,
             b: Optional[oracle.Backward], tokens: Optional[np.ndarray] = None,
-            rows: Optional[np.ndarray] = None) -> Report:
+            rows: Optional[np.ndarray] = None, want_bwd: bool = True) -> Report:
     """`tokens`: the token ids the oracle results r, f (and b.dh) cover, default all.  `rows`: the
-    neuron ids b.dK / b.dV cover (in that order), default all N."""
+    neuron ids b.dK / b.dV cover (in that order), default all N.  `b` is the oracle's backward on its own
+    selection; when some token is replayed the backward is computed here on the replayed selection instead
+    (also when b is None and want_bwd)."""
     c = t.cfg
     T, k, e, N, bs = c.T, c.top_k, c.top_e, c.N, c.block_size
     tok = np.arange(T) if tokens is None else np.asarray(tokens)
     rep = Report(c.name, c.dtype, len(tok))
     tol = TOL[c.dtype]
+    if f.cand_id is None:
+        raise ValueError("compare needs the oracle's candidate scores (forward(..., want_candidates=True))")
 
     # ---- structural invariants of the GPU result, all tokens
     gi = g["idx"]
@@ -237,63 +177,94 @@ def compare(t: synth.Tensors, g: Dict[str, np.ndarray], r: oracle.Route, f: orac
     if (g["act"] < 0).any():
         rep.invariant_errors.append("negative activation")
 
-    # ---- selections against the oracle, covered tokens
-    good = np.ones(len(tok), bool)       # tokens whose selections are identical
-    excl_neurons = set()
+    # ---- selections against the oracle, covered tokens.  idx_rep / score_rep: the selection the values are
+    # judged on -- the oracle's own, except for tokens inside the tie band, which take the HIP path's.
+    idx_rep = f.idx.copy()
+    score_rep = f.score.copy()
+    valid = np.ones(len(tok), bool)      # False: selection wrong outside the band
+    replayed = np.zeros(len(tok), bool)
     for n, tt in enumerate(tok):
+        cand_id, cand_score, last = f.cand_id[n], f.cand_score[n], f.score[n, k - 1]
         ob, gbt = set(r.block_idx[n].tolist()), set(gb[tt].tolist())
         if ob != gbt:
-            good[n] = False
             diff = np.array(sorted(ob ^ gbt))
-            if _band_ok(r.p[n][diff], r.block_score[n, e - 1]):
-                rep.block_band_tokens += 1
-            else:
+            if not _band_ok(r.p[n][diff], r.block_score[n, e - 1]):
                 rep.block_bad_tokens += 1
-            # every neuron either side picked for this token may differ
-            excl_neurons.update(f.idx[n].tolist()); excl_neurons.update(gi[tt].tolist())
-            continue
-        oi, git = set(f.idx[n].tolist()), set(gi[tt].tolist())
+                valid[n] = False
+                continue
+            rep.block_band_tokens += 1
+            # a valid routing that is not the oracle's: the oracle's steps 3-4 on the blocks the HIP path took
+            f1 = oracle.forward(t.h[tt:tt + 1], t.K, t.V, gb[tt:tt + 1], bs, k, want_candidates=True)
+            cand_id, cand_score, last = f1.cand_id[0], f1.cand_score[0], f1.score[0, k - 1]
+            idx_rep[n], score_rep[n] = f1.idx[0], f1.score[0]
+            replayed[n] = True
+        oi, git = set(idx_rep[n].tolist()), set(gi[tt].tolist())
         if oi != git:
-            good[n] = False
             diff = np.array(sorted(oi ^ git))
-            pos = np.searchsorted(f.cand_id[n], diff)
-            found = (pos < f.cand_id[n].size) & (f.cand_id[n][np.minimum(pos, f.cand_id[n].size - 1)] == diff)
-            if found.all() and _band_ok(f.cand_score[n][pos], f.score[n, k - 1]):
-                rep.idx_band_tokens += 1
-            else:
+            sc_diff, found = _lookup(cand_id, cand_score, diff)
+            if not (found and _band_ok(sc_diff, last)):
                 rep.idx_bad_tokens += 1
-            excl_neurons.update(diff.tolist())
+                valid[n] = False
+                continue
+            rep.idx_band_tokens += 1
+            idx_rep[n] = gi[tt]
+            score_rep[n], _ = _lookup(cand_id, cand_score, gi[tt])
+            replayed[n] = True
+
+    # ---- the oracle's values on idx_rep
+    out_o = f.out.copy()
+    if replayed.any():
+        rp = np.nonzero(replayed)[0]
+        out_o[rp] = oracle.apply_selection(t.h[tok[rp]], t.K, t.V, idx_rep[rp], bs)
+    full_cover = tokens is None
+    if want_bwd and full_cover and (b is None or replayed.any()) and valid.all():
+        b = oracle.backward(t.h, t.K, t.V, idx_rep, score_rep, t.dOut, bs, rows=rows)
+
+    # pairs at the ReLU kink: either branch of the derivative is right within fp32
+    scale = np.abs(score_rep).max(axis=1, keepdims=True)
+    kink = (np.abs(score_rep) <= TIE_BAND * scale) & t.h[tok].any(axis=1, keepdims=True)
+    rep.kink_pairs = int(kink.sum())
+    kink_tok = kink.any(axis=1)
+    kink_neurons = np.unique(idx_rep[kink])
 
     # ---- values
-    gt = tok[good]
+    gt = tok[valid]
     if gt.size:
-        # activations aligned by neuron id (oracle rows are ordered by score)
-        order = np.argsort(f.idx[good], axis=1)
-        o_act = np.take_along_axis(f.act[good], order, axis=1)
+        order = np.argsort(idx_rep[valid], axis=1)       # oracle rows are ordered by score, the HIP path's by id
+        o_act = np.take_along_axis(np.maximum(score_rep[valid], 0.0), order, axis=1)
         rep.err["act"] = rel_l2(g["act"][gt], o_act)
-        rep.err["block_score"] = rel_l2(g["block_score"][gt], r.block_score[good])
-        rep.err["out"] = rel_l2(g["out"][gt], f.out[good])
+        unre = valid & ~replayed
+        if unre.any():
+            rep.err["block_score"] = rel_l2(g["block_score"][tok[unre]], r.block_score[unre])
+        rep.err["out"] = rel_l2(g["out"][gt], out_o[valid])
+        w, at, z = row_check(g["out"][gt], out_o[valid], tol)
+        rep.row_err["out"], rep.zero_rows_not_zero["out"] = (w, int(gt[at]) if at >= 0 else -1), z
         if b is not None and b.dh is not None:
-            rep.err["dh"] = rel_l2(g["dh"][gt], b.dh[good])
+            rep.err["dh"] = rel_l2(g["dh"][gt], b.dh[valid])
+            w, at, z = row_check(g["dh"][gt], b.dh[valid], tol, skip=kink_tok[valid])
+            rep.row_err["dh"], rep.zero_rows_not_zero["dh"] = (w, int(gt[at]) if at >= 0 else -1), z
     if b is not None:
-        rws = np.arange(N) if rows is None else np.asarray(rows)
-        keep = np.array([j not in excl_neurons for j in rws.tolist()], bool)
-        if tokens is not None:
+        if not full_cover:
             # gradient rows need every token's selection: only valid when the oracle covered all tokens
             raise ValueError("row comparison needs oracle results for all tokens")
-        rep.excluded_rows = int((~keep).sum())
+        rws = np.arange(N) if rows is None else np.asarray(rows)
         o_touched = np.zeros(N, bool)
         o_touched[b.touched] = True
-        if not np.array_equal(o_touched[rws][keep], (~untouched)[rws][keep]):
-            rep.invariant_errors.append("touched differs from the oracle's outside the tie band")
-        sel = keep & (~untouched)[rws]
+        if valid.all() and not np.array_equal(o_touched[rws], (~untouched)[rws]):
+            rep.invariant_errors.append("touched differs from the oracle's")
+        sel = (~untouched)[rws] & o_touched[rws]
         if g.get("grad_rows") is not None:
             assert np.array_equal(g["grad_rows"], rws), "GPU gradient rows were fetched for other neurons"
             gK, gV = g["dK"], g["dV"]
         else:
             gK, gV = g["dK"][rws], g["dV"][rws]
+        rep.rows_compared = int(sel.sum())
         rep.err["dK"] = rel_l2(gK[sel], b.dK[sel])
         rep.err["dV"] = rel_l2(gV[sel], b.dV[sel])
+        skip = np.isin(rws[sel], kink_neurons)
+        for nm, gx, ox in (("dK", gK, b.dK), ("dV", gV, b.dV)):
+            w, at, z = row_check(gx[sel], ox[sel], tol, skip=skip if nm == "dK" else None)
+            rep.row_err[nm], rep.zero_rows_not_zero[nm] = (w, int(rws[sel][at]) if at >= 0 else -1), z
     return rep
 
 
@@ -310,5 +281,4 @@ def run_and_compare(cfg: synth.Config, rows: Optional[np.ndarray] = None) -> Rep
     g = run_gpu(t, rows=rows)
     r = oracle.route(t.h, t.Wg, cfg.top_e, t.bias)
     f = oracle.forward(t.h, t.K, t.V, r.block_idx, cfg.block_size, cfg.top_k, want_candidates=True)
-    b = oracle.backward(t.h, t.K, t.V, f.idx, f.score, t.dOut, cfg.block_size, rows=rows)
-    return compare(t, g, r, f, b, rows=rows)
+    return compare(t, g, r, f, None, rows=rows)

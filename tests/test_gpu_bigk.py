@@ -61,9 +61,10 @@ def test_exact_ties_across_sweep_tiles(P):
 def test_no_key_experts_at_scale(P):
     # 2048 tokens over one block of 65536 neurons (the keys and values of the LLaMA-7B-shaped configuration
     # without the router): the launch configuration bench.py times for this variant; every selection, out and dh
-    # are compared, dK / dV on 256 sampled rows
+    # are compared row by row, dK / dV on the first and last row, the rows at every 128-row boundary and 256
+    # random rows
     cfg = synth.CONFIGS["noke_bf16"]
-    rows = np.sort(np.random.default_rng(cfg.seed).choice(cfg.N, size=256, replace=False)).astype(np.int32)
+    rows = P.stratified_rows(cfg, 256)
     rep = P.run_and_compare(cfg, rows=rows)
     print(rep.summary(), flush=True)
     rep.assert_ok()

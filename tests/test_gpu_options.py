@@ -95,13 +95,18 @@ def test_everything_selected_on_the_matrix_core_path():
     assert P.rel_l2(g["dh"], dh) <= 2e-2 and P.rel_l2(g["dK"], dK) <= 2e-2 and P.rel_l2(g["dV"], dV) <= 2e-2
 
 
-def test_global_load_kernels_match_the_buffer_load_kernels(monkeypatch):
+def test_global_load_kernels_match_the_buffer_load_kernels():
     """The matrix-core kernels load operands below 4 GB through buffer resources and larger ones through global
-    pointers; MEFT_GLOBAL_LOADS=1 selects the latter at any size.  Both give the same bits."""
+    pointers; meft_debug_global_loads(1) selects the latter at any size.  Both give the same bits."""
+    from paper_2406_04984_amd import binding as B
     t = synth.make_inputs(synth.small_case(**CASES[1]))
     ref = P.run_gpu(t)
-    monkeypatch.setenv("MEFT_GLOBAL_LOADS", "1")
-    _same(ref, P.run_gpu(t))
+    B.meft_debug_global_loads(True)
+    try:
+        got = P.run_gpu(t)
+    finally:
+        B.meft_debug_global_loads(False)
+    _same(ref, got)
 
 
 def test_measurement_probes_run():

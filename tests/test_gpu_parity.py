@@ -37,13 +37,16 @@ def test_config_small_bf16(P):
 
 
 def _full_size(P, name, n_rows=384):
-    """The benchmark's launch configuration at full size: every token's selections, out and dh against the
-    oracle; dK / dV on a seeded sample of neuron rows (the oracle computes those rows one by one)."""
+    """The benchmark's launch configuration at full size: every token's selections, and out and dh row by row,
+    against the oracle; dK / dV on a stratified sample of neuron rows that the oracle computes one by one: of
+    every block the first and last neuron and the rows on both sides of every 128-row tile boundary, plus
+    seeded random rows."""
     cfg = synth.CONFIGS[name]
-    rows = np.sort(np.random.default_rng(cfg.seed).choice(cfg.N, size=n_rows, replace=False)).astype(np.int32)
+    rows = P.stratified_rows(cfg, n_rows)
     rep = P.run_and_compare(cfg, rows=rows)
     print(rep.summary(), flush=True)
     rep.assert_ok()
+    return rep
 
 
 @pytest.mark.timeout(900)
@@ -54,6 +57,19 @@ def test_config_llama7b_bf16_full_size(P):
 @pytest.mark.timeout(900)
 def test_config_wide_bf16_full_size(P):
     _full_size(P, "wide_bf16")
+
+
+@pytest.mark.timeout(900)
+def test_config_llama7b_hostkv_bf16_full_size(P):
+    """Keys and values (131072 x 4096, 128 blocks) in pinned host memory, gradients written back to pinned host
+    memory: the staged block copies, the kept copies in the backward and the row write-back at full size."""
+    _full_size(P, "llama7b_hostkv_bf16")
+
+
+def test_eight_blocks_per_token_on_the_matrix_core_path(P):
+    """top_e = 8: a token's output and input gradient are sums of eight per-block partial rows, each rounded to
+    bf16 before the fp32 sum (the rounding points the header states); judged row by row like everything else."""
+    _case(P, T=400, d=256, n_blocks=12, block_size=128, top_e=8, top_k=200, dtype="bf16", seed=707)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -1,6 +1,7 @@
 """Layer pipeline for host-resident keys and values: meft_hostkv_stage requests a layer's K, V blocks ahead of its
-forward (MEFT_FLAG_PRESTAGED), so that the transfer overlaps the previous layer's compute.  Same kernels and same
-data as the unpipelined calls, so every result must be bit-identical to them."""
+forward (MEFT_FLAG_PRESTAGED), so that the transfer overlaps the previous layer's compute.  Every layer's results
+are compared with the CPU oracle under the usual parity rules; the kernels and the data are those of the
+unpipelined calls, so the results must also be bit-identical to them."""
 import numpy as np
 import pytest
 
@@ -44,6 +45,11 @@ def test_prestaged_forward_and_kept_backward_are_bit_identical():
     B.meft_sparse_bwd(staged, layer.h, layer.K, layer.V, layer.idx, layer.act, layer.dOut, layer.dh, layer.dK, layer.dV,
                       layer.touched, layer.n_touched, layer.ws)
     got = layer.results()
+    from oracle import oracle
+    r, f, _ = oracle.layer(t, want_candidates=True)
+    rep = P.compare(t, got, r, f, None)
+    print(rep.summary(), flush=True)
+    rep.assert_ok()
     for n in NAMES:
         assert (ref[n] == got[n]).all(), n
 
@@ -71,8 +77,13 @@ def test_three_layers_pipelined():
         la = layers[l]
         B.meft_sparse_bwd(shapes[l], la.h, la.K, la.V, la.idx, la.act, la.dOut, la.dh, la.dK, la.dV, la.touched,
                           la.n_touched, la.ws)
+    from oracle import oracle
     for l, la in enumerate(layers):
         got = la.results()
+        r, f, _ = oracle.layer(ts[l], want_candidates=True)
+        rep = P.compare(ts[l], got, r, f, None)
+        print(f"layer {l}:", rep.summary(), flush=True)
+        rep.assert_ok()
         for n in NAMES:
             assert (refs[l][n] == got[n]).all(), (l, n)
 
