@@ -142,6 +142,23 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
                        void* stream);
 
 /*
+ * meft_route for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as meft_route, without
+ * `ws`: the partial router scores go to a fixed array of MEFT_ROUTE_STATIC_BYTES bytes of device memory that is
+ * part of the library's image (every GPU the library runs on holds its own copy until the process ends; its
+ * address is looked up once per device, on the first call with that device current).  The call allocates nothing,
+ * on the host or on the device, and creates no events (per-kernel timing is off inside it).
+ *   Limit: 16 * T * n_blocks <= MEFT_ROUTE_STATIC_BYTES (four partial score matrices of T x n_blocks floats);
+ *   beyond it MEFT_ERR_WORKSPACE and nothing is enqueued.
+ *   All calls on one GPU share that array: calls that overlap in time on one GPU (different streams, or host
+ *   threads on different streams) race; order them on one stream or with events.  Nothing in the array has to
+ *   start from zero and nothing in it is read after the call's kernels have finished.
+ */
+#define MEFT_ROUTE_STATIC_BYTES ((size_t)16 << 20)
+meft_status meft_route_static(const meft_shape* shape, const void* h, const void* Wg, const float* bias,
+                              int32_t* block_idx, float* block_score, void* stream);
+
+/*
  * Key scores inside the chosen blocks, top-k neuron selection, gather of the selected value rows
  * and the activation-weighted sum (Section 3.2 Eq. 6-7; Section 3.1 Eq. 1-4; Algorithm 1, inner
  * loop, TopK and the returned adapter term).

@@ -23,7 +23,8 @@ EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "me
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",
            "meft_probe_copy", "meft_probe_mfma", "meft_adam_rows", "meft_last_device_error",
            "meft_union_workspace_bytes", "meft_union_fwd", "meft_union_bwd", "meft_hostkv_stage",
-           "meft_debug_global_loads")
+           "meft_debug_global_loads", "meft_route_static")
+MEFT_ROUTE_STATIC_BYTES = 16 << 20
 
 
 class MeftShape(ctypes.Structure):
@@ -65,6 +66,8 @@ _lib.meft_status_string.restype = ctypes.c_char_p
 _lib.meft_status_string.argtypes = [ctypes.c_int]
 _lib.meft_route.restype = ctypes.c_int
 _lib.meft_route.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.meft_route_static.restype = ctypes.c_int
+_lib.meft_route_static.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.meft_sparse_fwd.restype = ctypes.c_int
 _lib.meft_sparse_fwd.argtypes = [_shape_p, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.meft_sparse_bwd.restype = ctypes.c_int
@@ -144,6 +147,14 @@ def meft_route(shape, h, Wg, bias, block_idx, block_score, ws, stream=None, chec
                          wp, wb, _stream(stream))
     if check and rc:
         raise MeftError("meft_route", rc)
+    return rc
+
+
+def meft_route_static(shape, h, Wg, bias, block_idx, block_score, stream=None, check=True) -> int:
+    rc = _lib.meft_route_static(ctypes.byref(shape), _p(h), _p(Wg), _p(bias), _p(block_idx), _p(block_score),
+                                _stream(stream))
+    if check and rc:
+        raise MeftError("meft_route_static", rc)
     return rc
 
 

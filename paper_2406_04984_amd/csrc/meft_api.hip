@@ -23,6 +23,10 @@
 #include "select.h"
 #include "union_path.h"
 
+// Device memory of meft_route_static: part of the library's image, one copy on every GPU the library runs on.  In
+// host code this name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[MEFT_ROUTE_STATIC_BYTES];
+
 namespace meft {
 namespace {
 
@@ -862,6 +866,40 @@ meft_status meft_route(const meft_shape* shape, const void* h, const void* Wg, c
   MEFT_API_LOCK();
   clear_stale_error();
   return route_impl(s, h, Wg, bias, block_idx, block_score, w.p, st);
+}
+
+// Address of `scratch` on the current device, looked up on the first call with that device current.
+static float* static_scratch_ptr() {
+  constexpr int kMaxDevices = 64;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    ptr[dev] = p;
+  }
+  return static_cast<float*>(ptr[dev]);
+}
+
+meft_status meft_route_static(const meft_shape* shape, const void* h, const void* Wg, const float* bias,
+                              int32_t* block_idx, float* block_score, void* stream) {
+  meft_status rc = check_shape(shape);
+  if (rc != MEFT_OK) return rc;
+  const meft_shape& s = *shape;
+  if (!h || !Wg || !block_idx || !aligned16(h) || !aligned16(Wg)) return MEFT_ERR_INVALID_ARG;
+  if (RouteWs(s, nullptr).bytes > MEFT_ROUTE_STATIC_BYTES) return MEFT_ERR_WORKSPACE;
+  if (s.T == 0) return MEFT_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  MEFT_API_LOCK();
+  clear_stale_error();
+  float* p = static_scratch_ptr();
+  if (!p) { (void)launch_status(); return MEFT_ERR_DEVICE; }
+  const bool timing = g_prof_on;   // per-kernel timing creates events: off inside this call
+  g_prof_on = false;
+  rc = route_impl(s, h, Wg, bias, block_idx, block_score, p, st);
+  g_prof_on = timing;
+  return rc;
 }
 
 meft_status meft_sparse_fwd(const meft_shape* shape, const void* h, const void* K, const void* V,
