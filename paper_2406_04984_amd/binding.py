@@ -18,6 +18,7 @@ MEFT_F32, MEFT_BF16 = 0, 1
 MEFT_FLAG_HOST_KV = 1
 MEFT_FLAG_KEEP_STAGED = 2
 MEFT_FLAG_PRESTAGED = 4
+MEFT_FLAG_REUSE_FWD = 8
 
 EXPORTS = ("meft_workspace_bytes", "meft_check_shape", "meft_status_string", "meft_route",
            "meft_sparse_fwd", "meft_sparse_bwd", "meft_profile_enable", "meft_profile_read",

@@ -31,6 +31,7 @@ constexpr int kSlotPad = 192;
 // the contraction is split `ksplit` ways over workgroups to fill the chip; split s writes its partial
 // scores to p + s*T*n_blocks and the top-e kernel adds the partials in a fixed order.
 struct ProbRouter {
+  static constexpr int kTM = kTMNeu, kSA = 3, kSB = 3;   // 128-row tiles: twice as many workgroups for a small problem
   static constexpr int kLoaders = 2;
   static constexpr bool kAMC = false;
   static constexpr bool kBNC = false;
@@ -76,6 +77,7 @@ constexpr int kTokScores = 0, kTokMasked = 1, kTokRelu = 2;
 
 template <int MODE>
 struct ProbTokKC {
+  static constexpr int kTM = kTMTok, kSA = MEFT_TOK_SA, kSB = MEFT_TOK_SB;
   static constexpr int kLoaders = 2;
   static constexpr bool kAMC = false;
   static constexpr bool kBNC = false;
@@ -150,6 +152,7 @@ struct ProbTokKC {
 // Token-major, B contiguous along n: part[slot, :] = A[slot, 0:bs] . W_b   (W = V: forward value sum;
 // W = K: dh).  A is slot-major [slots, bsp] with zero padding in columns bs..bsp.
 struct ProbTokNC {
+  static constexpr int kTM = kTMTok, kSA = MEFT_TOK_SA, kSB = MEFT_TOK_SB;
   static constexpr int kLoaders = 4;   // measured: 0.375 -> 0.339 ms (value sum) against two
   static constexpr bool kAMC = false;
   static constexpr bool kBNC = true;
@@ -193,6 +196,7 @@ struct ProbTokNC {
 // come from a row of zeros that the workspace keeps in front of the activation matrices, those of X are any valid
 // rows.  Only rows whose neuron is touched are written.
 struct ProbNeuTN {
+  static constexpr int kTM = kTMNeu, kSA = 3, kSB = 3;
   static constexpr int kLoaders = 4;   // measured: 0.425 -> 0.388 ms (dV) against two
   static constexpr bool kAMC = true;
   static constexpr bool kBNC = true;

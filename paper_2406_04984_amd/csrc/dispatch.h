@@ -63,7 +63,8 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int32_t* __restrict
                                                              int BM, int32_t* __restrict__ cnt,
                                                              int32_t* __restrict__ group_off,
                                                              int32_t* __restrict__ tile_off, int cap,
-                                                             int2* __restrict__ grp, int* __restrict__ len) {
+                                                             int2* __restrict__ grp, int* __restrict__ len,
+                                                             int sched_tile_m) {
   __shared__ int s_w[16];
   const int tid = threadIdx.x;   // = block, n_blocks <= 1024
   int tot = 0;
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int32_t* __restrict
   if (tid == 0) { group_off[n_blocks] = all_g; tile_off[n_blocks] = all_t; }
   if (grp != nullptr) {
     __syncthreads();   // group_off is read back below
-    build_sched_body(group_off, n_blocks, cap, grp, len);
+    build_sched_body(group_off, n_blocks, cap, grp, len, sched_tile_m);
   }
 }
 

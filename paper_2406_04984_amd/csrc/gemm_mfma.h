@@ -9,10 +9,14 @@
 //     dOut, h are contiguous in d: the value sum of Eq. 4, dh, dK, dV;
 //   A m-contiguous (rows indexed by k): dK, dV, whose A operand is the slot-major activation matrix, read as it is.
 //
-// Tile 128 (m) x 256 (n) x 64 (k); 4 compute waves as 2 x 2, each wave 64 x 128 = 2 x 4 MFMA tiles, plus two or
-// four loader waves that own the whole global -> LDS traffic (global_load_lds, 16 B per lane).  Three stages of 48 KB
-// form a ring.  LDS layouts are XOR-swizzled so that both the linear DMA writes and the fragment reads are free of
-// bank conflicts:
+// Tile TM (m) x 256 (n) x 64 (k) with TM = 192 for the token-major problems and 128 for the router and the
+// neuron-major problems (a policy's kTM); 4 compute waves as 2 x 2, each wave TM/2 x 128 = (TM/64) x 4 MFMA tiles,
+// plus two or four loader waves that own the whole global -> LDS traffic (16 B per lane).  The operands have a ring
+// each in LDS: kSA slots of TM x 64 for A, kSB slots of 256 x 64 for B (three and three with TM = 128, two and three
+// with TM = 192: 144 KB both ways).  The 192-row tile moves 22 % fewer operand bytes per flop than the 128-row one,
+// and operand delivery from L2 is what bounds these kernels; its accumulators (192 registers per lane) still leave
+// room for the loader waves on the same SIMDs, which a 256 x 256 tile's would not.  LDS layouts are XOR-swizzled so
+// that both the linear DMA writes and the fragment reads are free of bank conflicts:
 //   k-contiguous operand: rows of 64 k = 8 chunks of 16 B; logical chunk c of row r sits at chunk
 //     c ^ ((r >> 1) & 7); fragments are read with ds_read_b128.
 //   n-contiguous B: rows of 256 n = 32 chunks; logical chunk c of row k sits at chunk c ^ (2 * (k & 7));
@@ -20,9 +24,10 @@
 //     both are read with the transposing ds_read_b64_tr_b16, which hands lane i of a 16-lane group the four
 //     k-consecutive values of column i of a 4 x 16 block.
 //
-// The k tiles of all the tiles a workgroup works through form ONE stream through the ring: the loaders request
-// stream position s + 2 right after the barrier that hands position s to the compute waves, whether or not s + 2
-// belongs to the next output tile, so the operand pipeline never drains at a tile boundary.  There is exactly one
+// The k tiles of all the tiles a workgroup works through form ONE stream through the rings: right after the barrier
+// that hands position s to the compute waves the loaders request A of position s + kSA - 1 and B of position
+// s + kSB - 1 (the operand with the shorter lead first), whether or not those belong to the next output tile, so the
+// operand pipeline never drains at a tile boundary.  There is exactly one
 // workgroup barrier per k tile of the stream, executed by all the waves.  (An extra barrier at the end of every
 // tile, releasing its last stage before the stores so that the loaders request a third k tile during the epilogue,
 // was measured and did not pay.)
@@ -44,13 +49,25 @@
 
 namespace meft {
 
-constexpr int kTM = 128, kTN = 256, kTK = 64, kStages = 3;
-constexpr int kStageElems = (kTM + kTN) * kTK;                 // 24576 bf16 = 48 KB
-constexpr int kOperandLdsBytes = kStages * kStageElems * 2;    // 144 KB
+constexpr int kTN = 256, kTK = 64;
+#ifndef MEFT_TOK_TM
+#define MEFT_TOK_TM 128
+#define MEFT_TOK_SA 3
+#define MEFT_TOK_SB 3
+#endif
+constexpr int kTMTok = MEFT_TOK_TM;    // tile rows of the token-major problems (groups of tokens against a block's rows)
+constexpr int kTMNeu = 128;    // tile rows of the router and of the neuron-major problems
+constexpr int kBSlotElems = kTN * kTK;                         // one B slot: 32 KB
 constexpr int kIdRingSlots = 4;                                // k tiles of gathered-row numbers kept per loader
 constexpr int kMaxLoaders = 4;
-constexpr int kGemmLdsBytes = kOperandLdsBytes + kMaxLoaders * kIdRingSlots * 64 * 4;   // + 1 KB per loader
 constexpr int kXcd = 8;
+// LDS of a launch: the two operand rings and, where the numbers of gathered B rows travel through LDS, 1 KB per loader
+template <class P>
+constexpr int operand_lds_bytes() { return (P::kSA * P::kTM + P::kSB * kTN) * kTK * 2; }
+template <class P>
+constexpr int gemm_lds_bytes() {
+  return operand_lds_bytes<P>() + (P::kRowIdsInMemory ? kMaxLoaders * kIdRingSlots * 64 * 4 : 0);
+}
 // threads of a launch: four compute waves plus the policy's loader waves
 template <class P>
 constexpr int gemm_threads() { return 256 + 64 * P::kLoaders; }
@@ -77,6 +94,7 @@ struct TileCoord {
 };
 
 // A problem policy P provides:
+//   static constexpr int kTM, kSA, kSB;                 tile rows (128 or 192) and the slots of the A and B rings
 //   static constexpr int kLoaders;                      loader waves, 2 or 4
 //   __device__ bool locate(int wg, TileCoord&) const;   false: no tile with id wg, nor with any larger id on
 //                                                       the same XCD (ids wg + 8, wg + 16, ...)
@@ -186,7 +204,15 @@ __device__ __forceinline__ uint32_t byte_off(const uint16_t* ptr, const uint16_t
 template <class P, bool kBuf>
 __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
   constexpr int kLoaders = P::kLoaders;
+  constexpr int TM = P::kTM, SA = P::kSA, SB = P::kSB;
+  constexpr int MI = TM / 64;                       // 32-row MFMA tiles per compute wave: 2 or 3
+  constexpr int kASlotElems = TM * kTK;
+  constexpr int kBRing = SA * kASlotElems;          // element offset of the B ring
   static_assert(kLoaders == 2 || kLoaders == 4, "loader waves: 2 or 4");
+  static_assert(TM == 128 || TM == 192, "tile rows: 128 or 192");
+  static_assert(SA >= 2 && SA <= 3 && SB >= 2 && SB <= 3, "ring depths: 2 or 3");
+  static_assert(!P::kAMC || TM == 128, "the m-contiguous A layout is written for 128 rows");
+  static_assert(!P::kRowIdsInMemory || (SA == 3 && SB == 3), "row numbers through LDS: three slots each");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -200,24 +226,25 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
   if (wave >= 4) {
     // ------------------------------------------------------------------ loader waves
     const int lw = wave - 4;
-    constexpr int LA = kTM / 8 / kLoaders;   // A wave-loads (1 KB each) per loader and stage: 8 or 4
-    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (1 KB each) per loader and stage: 16 or 8
-    static_assert(LA + LB <= 63, "partial vmcnt wait out of range");
+    constexpr int LA = TM / 8 / kLoaders;    // A wave-loads (1 KB each) per loader and slot: 12, 8, 6 or 4
+    constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (1 KB each) per loader and slot: 16 or 8
+    constexpr int DA = SA - 1, DB = SB - 1;  // positions ahead of the barrier at which A and B are requested
+    constexpr int kAhead = (DA - 1) * LA + (DB - 1) * LB;   // loads that may still be in flight at a barrier
+    static_assert(kAhead <= 63, "partial vmcnt wait out of range");
     const int lr8 = lane >> 3;
-    int* idring = reinterpret_cast<int*>(smem + kOperandLdsBytes / 2) + lw * kIdRingSlots * 64;
+    int* idring = reinterpret_cast<int*>(smem + operand_lds_bytes<P>() / 2) + lw * kIdRingSlots * 64;
 
-    // Three cursors walk the same sequence of (tile, k tile) pairs: the row numbers of gathered B rows are
-    // requested three positions ahead of the barrier, the operands two positions ahead.
+    // Cursors over one and the same sequence of (tile, k tile) positions: the operand A, the operand B, and (where
+    // they sit in memory) the row numbers of gathered B rows, which run one position ahead of B.
+    struct Cursor {
+      int wg, k, n, slot;
+      bool ok;
+      TileCoord t;
+    };
+    Cursor ca{(int)blockIdx.x, 0, 0, 0, true, tc}, cb = ca, cd = ca;
+    cd.ok = P::kBNC && P::kRowIdsInMemory;
     //   consume: position handed to the compute waves at the next barrier
     int wg_c = blockIdx.x, nk_c = tc.nk;
-    //   operands
-    int wg_o = blockIdx.x, k_o = 0, n_o = 0, stage_o = 0;
-    bool ok_o = true;
-    TileCoord t_o = tc;
-    //   row numbers (only where they sit in memory)
-    int wg_d = blockIdx.x, k_d = 0, n_d = 0;
-    bool ok_d = P::kBNC && P::kRowIdsInMemory;
-    TileCoord t_d = tc;
 
     // A, k-contiguous: a wave-load covers 8 rows (m) x 128 bytes; fixed row pointers per tile, advanced by k.
     // A, m-contiguous: a wave-load covers 4 rows (k) x 256 bytes; lane l fetches the 16-byte chunk
@@ -239,11 +266,12 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     // instruction's scalar offset: the k offset of k-contiguous operands, the row offset of consecutive B rows.
     [[maybe_unused]] uint32_t oa[P::kAMC ? 4 : LA], ob[P::kBNC ? 4 : LB];
     const int half = lane >> 5;
-    auto setup = [&]() {
+    auto setup_a = [&]() {
+      const TileCoord& t = ca.t;
       if constexpr (kBuf) {
         if constexpr (P::kAMC) {
           const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
-          const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
+          const int col = t.m0 + chunk * 8, last = p.a_cols(t) - 8;
           const uint32_t o = byte_off(p.a_mat() + (col > last ? last : col), p.a_base());
 #pragma unroll
           for (int q = 0; q < 4; ++q) oa[q] = o;
@@ -251,53 +279,59 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
           for (int i = 0; i < LA; ++i) {
             const int row = (lw * LA + i) * 8 + lr8;
-            oa[i] = byte_off(p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3), p.a_base());
+            oa[i] = byte_off(p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3), p.a_base());
           }
         }
+      } else {
+        if constexpr (P::kAMC) {
+          const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
+          const int col = t.m0 + chunk * 8, last = p.a_cols(t) - 8;
+          const int acol = col > last ? last : col;                       // clamp (rows beyond Mrows are never stored)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) pa[q] = p.a_mat() + (acol - q * 512);
+        } else {
+#pragma unroll
+          for (int i = 0; i < LA; ++i) {
+            const int row = (lw * LA + i) * 8 + lr8;
+            pa[i] = p.a_row(t, t.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
+          }
+        }
+      }
+    };
+    auto setup_b = [&]() {
+      const TileCoord& t = cb.t;
+      if constexpr (kBuf) {
         if constexpr (P::kBNC) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
-            int col = t_o.n0 + chunk * 8;
-            col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;
+            int col = t.n0 + chunk * 8;
+            col = col > t.Ncols - 8 ? t.Ncols - 8 : col;
             ob[q] = byte_off(p.b_row_ptr(0) + col, p.b_base());
           }
         } else {
 #pragma unroll
           for (int i = 0; i < LB; ++i) {
             const int row = (lw * LB + i) * 8 + lr8;
-            ob[i] = byte_off(p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3), p.b_base());
+            ob[i] = byte_off(p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3), p.b_base());
           }
         }
       } else {
-      if constexpr (P::kAMC) {
-        const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
-        const int col = t_o.m0 + chunk * 8, last = p.a_cols(t_o) - 8;
-        const int acol = col > last ? last : col;                       // clamp (rows beyond Mrows are never stored)
+        if constexpr (P::kBNC) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) pa[q] = p.a_mat() + (acol - q * 512);
-      } else {
+          for (int q = 0; q < 4; ++q) {
+            const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
+            int col = t.n0 + chunk * 8;
+            col = col > t.Ncols - 8 ? t.Ncols - 8 : col;              // clamp (columns beyond Ncols are never stored)
+            pb[q] = p.b_row_ptr(0) + col - q * 512;
+          }
+        } else {
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-          const int row = (lw * LA + i) * 8 + lr8;
-          pa[i] = p.a_row(t_o, t_o.m0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
+          for (int i = 0; i < LB; ++i) {
+            const int row = (lw * LB + i) * 8 + lr8;
+            pb[i] = p.b_row(t, t.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
+          }
         }
-      }
-      if constexpr (P::kBNC) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
-          int col = t_o.n0 + chunk * 8;
-          col = col > t_o.Ncols - 8 ? t_o.Ncols - 8 : col;              // clamp (columns beyond Ncols are never stored)
-          pb[q] = p.b_row_ptr(0) + col - q * 512;
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          const int row = (lw * LB + i) * 8 + lr8;
-          pb[i] = p.b_row(t_o, t_o.n0 + row) + (((lane & 7) ^ ((row >> 1) & 7)) << 3) - (i & 3) * 512;
-        }
-      }
       }
     };
     // Where every operand matrix is smaller than 4 GB the loads are buffer loads (a wave-uniform resource descriptor,
@@ -327,25 +361,62 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 
     auto request_ids = [&]() {
       if constexpr (P::kBNC && P::kRowIdsInMemory) {
-        if (!ok_d) return;
-        __builtin_amdgcn_global_load_lds(MEFT_GPTR(p.b_row_id_src(t_d, k_d * kTK) + lane),
-                                         MEFT_LPTR(idring + (n_d & (kIdRingSlots - 1)) * 64), 4, 0, 0);
-        ++n_d;
-        if (++k_d == t_d.nk) { wg_d += step; k_d = 0; ok_d = next_tile(wg_d, t_d); }
+        if (!cd.ok) return;
+        __builtin_amdgcn_global_load_lds(MEFT_GPTR(p.b_row_id_src(cd.t, cd.k * kTK) + lane),
+                                         MEFT_LPTR(idring + (cd.n & (kIdRingSlots - 1)) * 64), 4, 0, 0);
+        ++cd.n;
+        if (++cd.k == cd.t.nk) { cd.wg += step; cd.k = 0; cd.ok = next_tile(cd.wg, cd.t); }
       }
     };
-    auto request_operands = [&]() {
-      if (!ok_o) return;
-      uint16_t* sa = smem + stage_o * kStageElems;
-      uint16_t* sb = sa + kTM * kTK;
+    // one k tile of A into the next slot of the A ring; false: the stream has ended, nothing was requested
+    auto request_a = [&]() -> bool {
+      if (!ca.ok) return false;
+      const TileCoord& t = ca.t;
+      uint16_t* my_a = smem + ca.slot * kASlotElems + lw * LA * 512;   // 512 elements = 1 KB per load
+      [[maybe_unused]] int a_row_bytes = 0;
+      if constexpr (P::kAMC) a_row_bytes = p.a_cols(t) * 2;
+      if constexpr (kBuf) {
+        const int k_bytes = ca.k * kTK * 2;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+          if constexpr (P::kAMC) {
+            const int row = p.a_krow(t, ca.k * kTK + 4 * (lw * LA + i) + (lane >> 4));
+            MEFT_LOAD_1K_BUF(rsrc_a, oa[i & 3] + (uint32_t)row * (uint32_t)a_row_bytes, 0, my_a, i);
+          } else {
+            MEFT_LOAD_1K_BUF(rsrc_a, oa[i], k_bytes, my_a, i);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+          if constexpr (P::kAMC) {
+            const int row = p.a_krow(t, ca.k * kTK + 4 * (lw * LA + i) + (lane >> 4));
+            MEFT_LOAD_1K(reinterpret_cast<const char*>(pa[i & 3]) + (int64_t)row * a_row_bytes, my_a, i);
+          } else {
+            MEFT_LOAD_1K(pa[i] + ca.k * kTK, my_a, i);
+          }
+        }
+      }
+      ++ca.n;
+      ca.slot = ca.slot + 1 == SA ? 0 : ca.slot + 1;
+      if (++ca.k == t.nk) {
+        ca.wg += step; ca.k = 0; ca.ok = next_tile(ca.wg, ca.t);
+        if (ca.ok) setup_a();
+      }
+      return true;
+    };
+    // one k tile of B into the next slot of the B ring
+    auto request_b = [&]() -> bool {
+      if (!cb.ok) return false;
+      const TileCoord& t = cb.t;
       // n-contiguous B: ids[i] = number of the B row this lane fetches in its i-th load,
-      // k = 64 * k_o + 2 * (lw * LB + i) + half
+      // k = 64 * cb.k + 2 * (lw * LB + i) + half
       int ids[LB];
       if constexpr (P::kBNC && P::kRowIdsInMemory) {
         // out of the ring; one asm block with its own wait (through plain loads the compiler would first drain every
         // outstanding operand load)
         const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(
-            idring + (n_o & (kIdRingSlots - 1)) * 64 + 2 * lw * LB + half);
+            idring + (cb.n & (kIdRingSlots - 1)) * 64 + 2 * lw * LB + half);
         if constexpr (LB == 16) {
         asm volatile(
             "ds_read_b32 %0, %16\n\tds_read_b32 %1, %16 offset:8\n\tds_read_b32 %2, %16 offset:16\n\t"
@@ -372,31 +443,19 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
         }
       } else if constexpr (P::kBNC) {
 #pragma unroll
-        for (int i = 0; i < LB; ++i) ids[i] = p.b_row_ids(t_o, k_o * kTK + 2 * (lw * LB + i) + half);
+        for (int i = 0; i < LB; ++i) ids[i] = p.b_row_ids(t, cb.k * kTK + 2 * (lw * LB + i) + half);
       }
-      [[maybe_unused]] int a_row_bytes = 0;
-      if constexpr (P::kAMC) a_row_bytes = p.a_cols(t_o) * 2;
-      uint16_t* my_a = sa + lw * LA * 512;   // 512 elements = 1 KB per load
-      uint16_t* my_b = sb + lw * LB * 512;
+      uint16_t* my_b = smem + kBRing + cb.slot * kBSlotElems + lw * LB * 512;
       if constexpr (kBuf) {
-        const int k_bytes = k_o * kTK * 2;
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-          if constexpr (P::kAMC) {
-            const int row = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4));
-            MEFT_LOAD_1K_BUF(rsrc_a, oa[i & 3] + (uint32_t)row * (uint32_t)a_row_bytes, 0, my_a, i);
-          } else {
-            MEFT_LOAD_1K_BUF(rsrc_a, oa[i], k_bytes, my_a, i);
-          }
-        }
+        const int k_bytes = cb.k * kTK * 2;
         if constexpr (P::kBNC) {
-          const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
+          const uint32_t row_bytes = (uint32_t)t.Ncols * 2u;
           bool linear = false;
           if constexpr (!P::kRowIdsInMemory) {
-            linear = p.b_rows_linear(t_o, k_o * kTK);
+            linear = p.b_rows_linear(t, cb.k * kTK);
             if (linear) {
               // 64 consecutive rows: this lane's row is first + 2 * (lw * LB + i) + half
-              const uint32_t first = (uint32_t)p.b_row_ids(t_o, k_o * kTK) * row_bytes, hoff = half * row_bytes;
+              const uint32_t first = (uint32_t)p.b_row_ids(t, cb.k * kTK) * row_bytes, hoff = half * row_bytes;
 #pragma unroll
               for (int i = 0; i < LB; ++i)
                 MEFT_LOAD_1K_BUF(rsrc_b, ob[i & 3] + hoff, (int)(first + 2u * (lw * LB + i) * row_bytes), my_b, i);
@@ -412,54 +471,58 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
           for (int i = 0; i < LB; ++i) MEFT_LOAD_1K_BUF(rsrc_b, ob[i], k_bytes, my_b, i);
         }
       } else {
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-          if constexpr (P::kAMC) {
-            const int row = p.a_krow(t_o, k_o * kTK + 4 * (lw * LA + i) + (lane >> 4));
-            MEFT_LOAD_1K(reinterpret_cast<const char*>(pa[i & 3]) + (int64_t)row * a_row_bytes, my_a, i);
-          } else {
-            MEFT_LOAD_1K(pa[i] + k_o * kTK, my_a, i);
-          }
-        }
         if constexpr (P::kBNC) {
-          const uint32_t row_bytes = (uint32_t)t_o.Ncols * 2u;
+          const uint32_t row_bytes = (uint32_t)t.Ncols * 2u;
 #pragma unroll
           for (int i = 0; i < LB; ++i)
             MEFT_LOAD_1K(reinterpret_cast<const char*>(pb[i & 3]) + (uint64_t)(uint32_t)ids[i] * row_bytes, my_b, i);
         } else {
 #pragma unroll
-          for (int i = 0; i < LB; ++i) MEFT_LOAD_1K(pb[i] + k_o * kTK, my_b, i);
+          for (int i = 0; i < LB; ++i) MEFT_LOAD_1K(pb[i] + cb.k * kTK, my_b, i);
         }
       }
-      ++n_o;
-      stage_o = stage_o + 1 == kStages ? 0 : stage_o + 1;
-      if (++k_o == t_o.nk) {
-        wg_o += step; k_o = 0; ok_o = next_tile(wg_o, t_o);
-        if (ok_o) setup();
+      ++cb.n;
+      cb.slot = cb.slot + 1 == SB ? 0 : cb.slot + 1;
+      if (++cb.k == t.nk) {
+        cb.wg += step; cb.k = 0; cb.ok = next_tile(cb.wg, cb.t);
+        if (cb.ok) setup_b();
       }
+      return true;
+    };
+    // the requests that follow a barrier: one k tile of each operand, the one with the shorter lead first, so that
+    // the loads which may still be in flight at the next barrier are the most recent ones.  true: both were made.
+    auto request_batch = [&]() -> bool {
+      request_ids();
+      bool a, b;
+      if constexpr (DA <= DB) { a = request_a(); b = request_b(); }
+      else { b = request_b(); a = request_a(); }
+      return a && b;
     };
 
-    setup();
+    setup_a();
+    setup_b();
     if constexpr (P::kBNC && P::kRowIdsInMemory) {
 #pragma unroll
-      for (int s = 0; s < kStages; ++s) request_ids();
+      for (int s = 0; s < DB + 1; ++s) request_ids();
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
+    // before the first barrier: position 0 of both operands first, then the positions the leads reach
+    bool full = request_a();
+    full = request_b() && full;
 #pragma unroll
-    for (int s = 0; s < kStages - 1; ++s) request_operands();
+    for (int s = 1; s < DA; ++s) full = request_a() && full;
+#pragma unroll
+    for (int s = 1; s < DB; ++s) full = request_b() && full;
 
-    int n_c = 0;   // positions handed over so far
     for (;;) {
       for (int kt = 0; kt < nk_c; ++kt) {
-        // position n_c has landed once at most the LA + LB loads of position n_c + 1 are outstanding (the counter
-        // retires in issue order, and the row numbers of a later position are requested before those loads); with
-        // nothing requested beyond n_c, everything is awaited
-        if (n_o > n_c + 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
+        // The position handed over now has landed once at most the kAhead most recent loads are outstanding (the
+        // counter retires in issue order), provided the last batch of requests was complete; near the end of the
+        // stream everything is awaited.
+        if (full) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kAhead) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        // every compute wave is past position n_c - 1: its stage takes position n_c + 2
-        request_ids();
-        request_operands();
-        ++n_c;
+        // every compute wave is past the previous position: its slots are free
+        full = request_batch();
       }
       wg_c += step;
       TileCoord t;
@@ -469,17 +532,18 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
   }
 
   // -------------------------------------------------------------------- compute waves
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 128;
+  constexpr int WM = TM / 2;   // rows of a compute wave: 64 or 96
+  const int wm = (wave >> 1) * WM, wn = (wave & 1) * 128;
   const int fr = lane & 31, fc = lane >> 5;
-  // k-contiguous operands: element offsets of this lane's fragment rows inside a stage, and their swizzle keys
-  int offA[2], keyA[2], offB[4], keyB[4];
+  // k-contiguous operands: element offsets of this lane's fragment rows inside a slot, and their swizzle keys
+  int offA[MI], keyA[MI], offB[4], keyB[4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) { const int r = wm + i * 32 + fr; offA[i] = r * kTK; keyA[i] = (r >> 1) & 7; }
+  for (int i = 0; i < MI; ++i) { const int r = wm + i * 32 + fr; offA[i] = r * kTK; keyA[i] = (r >> 1) & 7; }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) { const int r = wn + j * 32 + fr; offB[j] = kTM * kTK + r * kTK; keyB[j] = (r >> 1) & 7; }
-  // m- / n-contiguous operands: LDS byte offsets (A: inside a stage, B: inside its B region) of this lane's
-  // transposing reads.  Lane s of a 16-lane group points at row (k base + s/4), columns 4*(s%4)..+3 of a 4 x 16
-  // block and receives column s of that block, four consecutive k.  Low half: k = 8*(lane/32) + 0..3, high half +4.
+  for (int j = 0; j < 4; ++j) { const int r = wn + j * 32 + fr; offB[j] = r * kTK; keyB[j] = (r >> 1) & 7; }
+  // m- / n-contiguous operands: LDS byte offsets (inside a slot) of this lane's transposing reads.  Lane s of a
+  // 16-lane group points at row (k base + s/4), columns 4*(s%4)..+3 of a 4 x 16 block and receives column s of that
+  // block, four consecutive k.  Low half: k = 8*(lane/32) + 0..3, high half +4.
   uint32_t tra_lo[2], tra_hi[2], tr_lo[4], tr_hi[4];
   {
     const int gq = lane >> 4, s = lane & 15;
@@ -487,8 +551,8 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int m = wm + i * 32 + 16 * (gq & 1) + 4 * (s & 3);
-      tra_lo[i] = (uint32_t)(k_lo * kTM + (((m >> 3) ^ (4 * (k_lo & 3))) << 3) + (m & 7)) * 2u;
-      tra_hi[i] = (uint32_t)(k_hi * kTM + (((m >> 3) ^ (4 * (k_hi & 3))) << 3) + (m & 7)) * 2u;
+      tra_lo[i] = (uint32_t)(k_lo * TM + (((m >> 3) ^ (4 * (k_lo & 3))) << 3) + (m & 7)) * 2u;
+      tra_hi[i] = (uint32_t)(k_hi * TM + (((m >> 3) ^ (4 * (k_hi & 3))) << 3) + (m & 7)) * 2u;
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -499,43 +563,46 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
   }
 
   int wg = blockIdx.x;
-  int stage = 0;   // runs on across tiles, like the loaders' stage_o
+  int slot_a = 0, slot_b = 0;   // run on across tiles, like the loaders' slots
   for (;;) {
-    // lane l: the tag of row wm + l of this tile.  Asked before the k loop, so that a policy's memory read has long
-    // returned when the answer is needed.
+    // lane l: the tag of row wm + l of this tile (and, with 96 rows per wave, lane l < 32: of row wm + 64 + l).
+    // Asked before the k loop, so that a policy's memory read has long returned when the answer is needed.
     const int my_tag = p.row_tag(tc, tc.m0 + wm + lane);
+    [[maybe_unused]] int my_tag_hi = 0;
+    if constexpr (WM > 64) my_tag_hi = lane < WM - 64 ? p.row_tag(tc, tc.m0 + wm + 64 + lane) : 0;
 
-    f32x16 acc[2][4];
+    f32x16 acc[MI][4];
     const int nk = tc.nk;
     bool more = false;
     TileCoord tn;
-    // one k tile out of stage `stage`; kFirst: the first k16 step starts from zero instead of from acc (the matrix
-    // instruction takes the constant as its addend, so the accumulators are never cleared by hand)
+    // one k tile out of the current slots; kFirst: the first k16 step starts from zero instead of from acc (the
+    // matrix instruction takes the constant as its addend, so the accumulators are never cleared by hand)
     auto k_tile = [&](auto first_tag) {
       constexpr bool kFirst = decltype(first_tag)::value;
-      const uint16_t* st = smem + stage * kStageElems;
+      const uint16_t* sta = smem + slot_a * kASlotElems;
+      const uint16_t* stb = smem + kBRing + slot_b * kBSlotElems;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 fa[2], fb[4];
+        bf16x8 fa[MI], fb[4];
         const int c = ks * 2 + fc;   // k-contiguous operands: this lane's 16-byte chunk of the k16 step
         if constexpr (!P::kAMC) {
 #pragma unroll
-          for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&st[offA[i] + ((c ^ keyA[i]) << 3)]);
+          for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sta[offA[i] + ((c ^ keyA[i]) << 3)]);
         }
         if constexpr (!P::kBNC) {
           static_assert(!P::kAMC || P::kBNC, "an m-contiguous A comes with an n-contiguous B");
 #pragma unroll
-          for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&st[offB[j] + ((c ^ keyB[j]) << 3)]);
+          for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&stb[offB[j] + ((c ^ keyB[j]) << 3)]);
         } else {
           // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 bytes); that changes neither
           // (k & 7) nor (k & 3), so the swizzles hold
-          const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st + kTM * kTK);
+          const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(stb);
           uint32_t alo[4], ahi[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
           u32x2 o[8];
           if constexpr (P::kAMC) {
-            const uint32_t abase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(st);
+            const uint32_t abase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(sta);
             const uint32_t xa[4] = {abase + tra_lo[0], abase + tra_hi[0], abase + tra_lo[1], abase + tra_hi[1]};
             u32x2 oa[4];
             if (ks == 0) tr_read12<0, 0>(oa, o, xa, alo, ahi);
@@ -560,7 +627,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
           }
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             if (kFirst && ks == 0) {
@@ -571,7 +638,8 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
             }
           }
       }
-      stage = stage + 1 == kStages ? 0 : stage + 1;
+      slot_a = slot_a + 1 == SA ? 0 : slot_a + 1;
+      slot_b = slot_b + 1 == SB ? 0 : slot_b + 1;
     };
     MEFT_BARRIER_LDS();   // the loaders have seen the tile's first k tile land
     wg += step;
@@ -586,13 +654,14 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     // and n = wn + j*32 + lane%32.  For a register pair (r, r+1), r even, an even lane (column c) keeps its value of
     // row m and takes its right neighbour's value of that row; the odd lane (column c+1) keeps its value of row m+1
     // and takes its left neighbour's (DPP quad_perm [1,0,3,2] swaps neighbours).  Both then hold columns (c, c+1) of
-    // one row.  Per half of the accumulators (i) the rows' tags and whatever the policy reads per element (load_aux:
-    // unconditional loads, all in flight together) are fetched first, then the values are exchanged and stored.
+    // one row.  Per 32 rows of the accumulators (i), four register pairs at a time, the rows' tags and whatever the
+    // policy reads per element (load_aux: unconditional loads, all in flight together) are fetched first, then the
+    // values are exchanged and stored.
     {
       const bool odd = (lane & 1) != 0;
       const int nj = (p.out_cols(tc) - (tc.n0 + wn) + 31) / 32;   // 32-column fragments of this wave with stored columns
       const int ncol = tc.n0 + wn + (fr & ~1);
-      // row of this lane inside the wave's 64 = lane_row + a constant of the register pair
+      // row of this lane inside the wave's rows = lane_row + a constant of the register pair
       const int lane_row = fc * 4 + (lane & 1);
       [[maybe_unused]] size_t lane_at = 0;
       [[maybe_unused]] int ld = 0;
@@ -601,64 +670,72 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
         lane_at = p.row_off(tc, 1, tc.m0 + wm + lane_row) + ncol;   // one multiplication per tile
       }
       [[maybe_unused]] const unsigned long long ok_mask = __ballot(my_tag != 0);
+      [[maybe_unused]] const unsigned long long ok_mask_hi = __ballot(my_tag_hi != 0);
       auto epilogue = [&](auto full_tag) {
         constexpr bool kFull = decltype(full_tag)::value;   // all four fragments of the wave lie inside the output
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          int tag[8];
-          uint32_t aux[8][4];
+        for (int i = 0; i < MI; ++i) {
 #pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const int r = 2 * q;
-            const int rl = i * 32 + (r >> 2) * 8 + (r & 3) + lane_row;
-            // the row's tag: a bit of the wave's ballot where it only says "stored or not" (no trip through the LDS
-            // pipeline, which the loaders keep busy), a lane permute where it carries a number
-            if constexpr (P::kRowsLinear) tag[q] = (int)((ok_mask >> rl) & 1ull);
-            else tag[q] = __builtin_amdgcn_ds_bpermute(rl << 2, my_tag);
-            if constexpr (P::kAux) {
+          for (int qh = 0; qh < 2; ++qh) {
+            int tag[4];
+            uint32_t aux[4][4];
 #pragma unroll
-              for (int j = 0; j < 4; ++j) aux[q][j] = p.load_aux(tc, tc.m0 + wm + rl, ncol + 32 * j);
-            } else {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) aux[q][j] = 0u;
-            }
-          }
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const int r = 2 * q;
-            const int rc = i * 32 + (r >> 2) * 8 + (r & 3);   // the register pair's constant part of the row
-            [[maybe_unused]] uint32_t pk[4];
-            [[maybe_unused]] float lo[4], hi[4];
-            if constexpr (P::kOutBf16) {
-              // bf16 output: both rows' values of this lane's column are packed first, (row m | row m+1 << 16); one
-              // neighbour swap of the packed word and one byte permute give (column c | column c+1 << 16) of the
-              // lane's row (even lanes: row m from the low halves, odd lanes: row m+1 from the high halves)
-              const uint32_t sel = odd ? 0x03020706u : 0x05040100u;   // bytes 0-3: own word, 4-7: the neighbour's
-#pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                const uint32_t own = pack_bf16x2(acc[i][j][r], acc[i][j][r + 1]);
-                const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp((int)own, (int)own, 0xB1, 0xF, 0xF, true);
-                pk[j] = __builtin_amdgcn_perm(nb, own, sel);
+            for (int qq = 0; qq < 4; ++qq) {
+              const int r = 2 * (qh * 4 + qq);
+              const int rl = i * 32 + (r >> 2) * 8 + (r & 3) + lane_row;
+              // the row's tag: a bit of the wave's ballot where it only says "stored or not" (no trip through the LDS
+              // pipeline, which the loaders keep busy), a lane permute where it carries a number
+              if constexpr (P::kRowsLinear) {
+                tag[qq] = i < 2 ? (int)((ok_mask >> rl) & 1ull) : (int)((ok_mask_hi >> (rl - 64)) & 1ull);
+              } else {
+                tag[qq] = i < 2 ? __builtin_amdgcn_ds_bpermute(rl << 2, my_tag)
+                                : __builtin_amdgcn_ds_bpermute((rl - 64) << 2, my_tag_hi);
               }
-            } else {
+              if constexpr (P::kAux) {
 #pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
-                const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
-                const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
-                lo[j] = odd ? bn : a;
-                hi[j] = odd ? b : an;
+                for (int j = 0; j < 4; ++j) aux[qq][j] = p.load_aux(tc, tc.m0 + wm + rl, ncol + 32 * j);
+              } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) aux[qq][j] = 0u;
               }
             }
-            if (tag[q] != 0) {
-              size_t at;
-              if constexpr (P::kRowsLinear) at = lane_at + (size_t)(rc * ld);   // rc * ld: scalar arithmetic
-              else at = p.row_off(tc, tag[q], tc.m0 + wm + rc + lane_row) + ncol;
 #pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                if (kFull || j < nj) {
-                  if constexpr (P::kOutBf16) p.store_pk(at + 32 * j, ncol + 32 * j, pk[j], aux[q][j]);
-                  else p.store2(at + 32 * j, ncol + 32 * j, lo[j], hi[j], aux[q][j]);
+            for (int qq = 0; qq < 4; ++qq) {
+              const int r = 2 * (qh * 4 + qq);
+              const int rc = i * 32 + (r >> 2) * 8 + (r & 3);   // the register pair's constant part of the row
+              [[maybe_unused]] uint32_t pk[4];
+              [[maybe_unused]] float lo[4], hi[4];
+              if constexpr (P::kOutBf16) {
+                // bf16 output: both rows' values of this lane's column are packed first, (row m | row m+1 << 16); one
+                // neighbour swap of the packed word and one byte permute give (column c | column c+1 << 16) of the
+                // lane's row (even lanes: row m from the low halves, odd lanes: row m+1 from the high halves)
+                const uint32_t sel = odd ? 0x03020706u : 0x05040100u;   // bytes 0-3: own word, 4-7: the neighbour's
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  const uint32_t own = pack_bf16x2(acc[i][j][r], acc[i][j][r + 1]);
+                  const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp((int)own, (int)own, 0xB1, 0xF, 0xF, true);
+                  pk[j] = __builtin_amdgcn_perm(nb, own, sel);
+                }
+              } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  const float a = acc[i][j][r], b = acc[i][j][r + 1];   // plain copies: the values go to the builtin as floats
+                  const float an = __builtin_amdgcn_update_dpp(a, a, 0xB1, 0xF, 0xF, true);   // the neighbour's a
+                  const float bn = __builtin_amdgcn_update_dpp(b, b, 0xB1, 0xF, 0xF, true);   // the neighbour's b
+                  lo[j] = odd ? bn : a;
+                  hi[j] = odd ? b : an;
+                }
+              }
+              if (tag[qq] != 0) {
+                size_t at;
+                if constexpr (P::kRowsLinear) at = lane_at + (size_t)(rc * ld);   // rc * ld: scalar arithmetic
+                else at = p.row_off(tc, tag[qq], tc.m0 + wm + rc + lane_row) + ncol;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                  if (kFull || j < nj) {
+                    if constexpr (P::kOutBf16) p.store_pk(at + 32 * j, ncol + 32 * j, pk[j], aux[qq][j]);
+                    else p.store2(at + 32 * j, ncol + 32 * j, lo[j], hi[j], aux[qq][j]);
+                  }
                 }
               }
             }
@@ -675,7 +752,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 
 // ---- tile schedule shared by the grouped problems ----------------------------------------------
 // Every non-empty group (block of neurons with its tokens) is given to one XCD; XCD x works through its list
-// in order.  grp[x][i] = (group, number of m tiles of the groups before it in this list); an end entry
+// in order.  grp[x][i] = (group, number of m tiles -- of tile_m rows -- of the groups before it in this list); an end entry
 // (-1, total m tiles) closes the list.  Inside a group the m tiles vary fastest, so that the tiles that share a
 // B panel (one n tile of the group's block) run at the same time and the panel is read from HBM once.
 //
@@ -694,7 +771,7 @@ constexpr int kSchedSortMax = 1024;   // up to this many groups are dealt out lo
 
 // Executed by one whole workgroup of 1024 threads.
 __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ group_off, int n_groups, int cap,
-                                                 int2* __restrict__ grp, int* __restrict__ len) {
+                                                 int2* __restrict__ grp, int* __restrict__ len, int tile_m) {
   __shared__ int s_rows[kSchedSortMax];
   __shared__ int s_order[kSchedSortMax];
   __shared__ int s_sorted[kSchedSortMax];
@@ -728,7 +805,7 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
           if (lane < kXcd) {
             grp[(size_t)lane * cap + n] = make_int2(g, tiles);
             n += 1;
-            tiles += (r + kTM - 1) / kTM;
+            tiles += (r + tile_m - 1) / tile_m;
           }
           continue;
         }
@@ -739,7 +816,7 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
         if (lane == (key & (kXcd - 1))) {   // true in one of the lanes 0..7 only: the higher lanes hold 0x7FFFFFFF
           grp[(size_t)lane * cap + n] = make_int2(g, tiles);
           n += 1;
-          tiles += (r + kTM - 1) / kTM;
+          tiles += (r + tile_m - 1) / tile_m;
           load += (r + 63) / 64 + 2;
         }
       }
@@ -756,7 +833,7 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
       const int rows = group_off[g + 1] - group_off[g];
       if (rows == 0) continue;
       grp[(size_t)x * cap + n++] = make_int2(g, tiles);
-      tiles += (rows + kTM - 1) / kTM;
+      tiles += (rows + tile_m - 1) / tile_m;
     }
     grp[(size_t)x * cap + n] = make_int2(-1, tiles);
     len[x] = n;
@@ -764,8 +841,9 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
 }
 
 __global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups,
-                                                           int cap, int2* __restrict__ grp, int* __restrict__ len) {
-  build_sched_body(group_off, n_groups, cap, grp, len);
+                                                           int cap, int2* __restrict__ grp, int* __restrict__ len,
+                                                           int tile_m) {
+  build_sched_body(group_off, n_groups, cap, grp, len, tile_m);
 }
 
 __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,

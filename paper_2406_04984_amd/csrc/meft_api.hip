@@ -85,7 +85,8 @@ meft_status check_shape(const meft_shape* s) {
   if ((int64_t)s->T * s->top_k >= (1ll << 31) || (int64_t)s->T * C >= (1ll << 31)) return MEFT_ERR_INVALID_ARG;
   if (s->dtype != MEFT_F32 && s->dtype != MEFT_BF16) return MEFT_ERR_INVALID_ARG;
   if (s->activation != 0) return MEFT_ERR_INVALID_ARG;
-  if (s->flags & ~(uint32_t)(MEFT_FLAG_HOST_KV | MEFT_FLAG_KEEP_STAGED | MEFT_FLAG_PRESTAGED)) return MEFT_ERR_INVALID_ARG;
+  if (s->flags & ~(uint32_t)(MEFT_FLAG_HOST_KV | MEFT_FLAG_KEEP_STAGED | MEFT_FLAG_PRESTAGED | MEFT_FLAG_REUSE_FWD))
+    return MEFT_ERR_INVALID_ARG;
   if ((s->flags & (MEFT_FLAG_KEEP_STAGED | MEFT_FLAG_PRESTAGED)) && !(s->flags & MEFT_FLAG_HOST_KV))
     return MEFT_ERR_INVALID_ARG;
   if (s->d % 8 != 0 || s->d > kMaxD || C > kMaxC || s->n_blocks > kMaxBlocks) return MEFT_ERR_UNSUPPORTED;
@@ -113,7 +114,7 @@ struct Carver {
 // The score contraction alone runs on the matrix-core kernel of the block-dense path also for bf16 shapes that
 // are not dense enough for the rest of it, when the groups are large enough to fill its 128-row tiles.
 bool use_mfma_scores(const meft_shape& s) {
-  return s.dtype == MEFT_BF16 && s.d % kTK == 0 && (int64_t)s.T * s.top_e >= (int64_t)kTM * s.n_blocks;
+  return s.dtype == MEFT_BF16 && s.d % kTK == 0 && (int64_t)s.T * s.top_e >= (int64_t)128 * s.n_blocks;
 }
 
 bool use_dense(const meft_shape& s) {
@@ -125,7 +126,7 @@ bool use_dense(const meft_shape& s) {
 int round64(int v) { return (v + 63) & ~63; }
 // per XCD: at most n_blocks groups (+1 end entry) and, as a bound that needs no knowledge of the deal, all m tiles
 int sched_cap(const meft_shape& s) { return s.n_blocks + 1; }
-int sched_max_tiles(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTM + s.n_blocks); }
+int sched_max_tiles(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTMTok + s.n_blocks); }
 // bound of the tile ids of a launch with tn n tiles per m tile (ids beyond the real ones find no tile)
 int tile_bound(const meft_shape& s, int tn) {
   const int64_t b = (int64_t)kXcd * sched_max_tiles(s) * tn;
@@ -171,50 +172,49 @@ struct DispatchWs {
   }
 };
 
-struct FwdWs : DispatchWs {
+// Block-dense path: what forward and backward both hold, at the same place in the workspace, so that a backward may
+// take the forward's dispatch tables and activation rows as they are (MEFT_FLAG_REUSE_FWD).
+struct DenseWs : DispatchWs {
+  int32_t *flag = nullptr, *chunk_cnt = nullptr;
+  uint16_t *zrow = nullptr, *Ap = nullptr, *DS = nullptr, *part = nullptr;
+  void carve_dense(const meft_shape& s, Carver& c) {
+    carve(s, c);
+    const size_t n_ent = (size_t)s.T * s.top_e;
+    chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
+    flag = c.take<int32_t>(s.N);                               // flag and zrow adjacent: cleared by one fill
+    // one piece: the row of zeros, A', DS', each row bsp elements, so that the zero row is row -1 of A' and row
+    // -(n_ent + 1) of DS'
+    const size_t bsp = round64(s.block_size);
+    zrow = c.take<uint16_t>(bsp * (1 + 2 * n_ent));
+    Ap = zrow ? zrow + bsp : nullptr;
+    DS = zrow ? Ap + n_ent * bsp : nullptr;
+    part = c.take<uint16_t>(n_ent * s.d);   // per-entry partial rows [T*e, d] bf16
+  }
+};
+
+struct FwdWs : DenseWs {
   float* sc;
-  uint16_t* Ap;   // dense path: A' [T*e, bsp]
-  uint16_t* part; // dense path: per-entry partial outputs [T*e, d] bf16
   size_t bytes;
   FwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
-    carve(s, c);
-    const size_t n_ent = (size_t)s.T * s.top_e;
-    sc = c.take<float>(n_ent * s.block_size);
-    Ap = nullptr; part = nullptr;
-    if (use_dense(s)) {
-      Ap = c.take<uint16_t>(n_ent * round64(s.block_size));
-      part = c.take<uint16_t>(n_ent * s.d);
-    }
+    if (use_dense(s)) carve_dense(s, c);
+    else carve(s, c);
+    sc = c.take<float>((size_t)s.T * s.top_e * s.block_size);
     bytes = c.off;
   }
 };
 
-struct BwdWs : DispatchWs {
+struct BwdWs : DenseWs {
   // gather path
   float* ds;
   int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted;
-  // dense path
-  int32_t *flag, *chunk_cnt;
-  uint16_t *zrow, *Ap, *DS, *part;
   size_t bytes;
   BwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
     const size_t P = (size_t)s.T * s.top_k;
-    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = flag = chunk_cnt = nullptr;
-    zrow = Ap = DS = nullptr; part = nullptr;
+    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = nullptr;
     if (use_dense(s)) {
-      carve(s, c);
-      const size_t n_ent = (size_t)s.T * s.top_e;
-      chunk_cnt = c.take<int32_t>((size_t)(s.N + kFlagChunk - 1) / kFlagChunk);
-      flag = c.take<int32_t>(s.N);                               // flag and zrow adjacent: cleared by one fill
-      // one piece: the row of zeros, A', DS', each row bsp elements, so that the zero row is row -1 of A' and row
-      // -(n_ent + 1) of DS'
-      const size_t bsp = round64(s.block_size);
-      zrow = c.take<uint16_t>(bsp * (1 + 2 * n_ent));
-      Ap = zrow ? zrow + bsp : nullptr;
-      DS = zrow ? Ap + n_ent * bsp : nullptr;
-      part = c.take<uint16_t>(n_ent * s.d);
+      carve_dense(s, c);
     } else {
       ds = c.take<float>(P);
       cnt_n = c.take<int32_t>(s.N);     // cnt_n and cursor are adjacent: cleared by one fill
@@ -468,17 +468,17 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
   static std::once_flag configured;  // raise the dynamic LDS limit of both instantiations once
   std::call_once(configured, [] {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, gemm_lds_bytes<P>());
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mfma_kernel<P, true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+                              hipFuncAttributeMaxDynamicSharedMemorySize, gemm_lds_bytes<P>());
   });
   // persistent workgroups: one per compute unit (the LDS footprint allows no more), each walking the tile ids
   // wg, wg + 256, ... below `grid`
   const int launch = grid < kPersistentWgs ? grid : kPersistentWgs;
   if (prob.buf) {
-    MEFT_LAUNCH(name, (gemm_mfma_kernel<P, true>), dim3(launch), dim3(gemm_threads<P>()), kGemmLdsBytes, st, prob, grid);
+    MEFT_LAUNCH(name, (gemm_mfma_kernel<P, true>), dim3(launch), dim3(gemm_threads<P>()), gemm_lds_bytes<P>(), st, prob, grid);
   } else {
-    MEFT_LAUNCH(name, (gemm_mfma_kernel<P, false>), dim3(launch), dim3(gemm_threads<P>()), kGemmLdsBytes, st, prob, grid);
+    MEFT_LAUNCH(name, (gemm_mfma_kernel<P, false>), dim3(launch), dim3(gemm_threads<P>()), gemm_lds_bytes<P>(), st, prob, grid);
   }
 }
 
@@ -492,7 +492,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
                 s.n_blocks, w.chunk_hist);
     MEFT_LAUNCH("dispatch_scan", dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, w.chunk_hist, n_chunks,
                 s.n_blocks, BM, w.cnt, w.group_off, w.tile_off, sched_cap(s), want_sched ? w.sched_pairs : nullptr,
-                w.sched_len);
+                w.sched_len, kTMTok);
     MEFT_LAUNCH("dispatch_place", dispatch_place_kernel, dim3(n_chunks), dim3(1024), lds, st, w.sblk, n_ent,
                 s.n_blocks, s.top_e, w.chunk_hist, w.group_off, w.perm, dense ? w.tok_of_slot : nullptr,
                 w.slot_of_ent, kSlotPad);
@@ -507,7 +507,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
   }
   if (want_sched) {
     MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks,
-                sched_cap(s), w.sched_pairs, w.sched_len);
+                sched_cap(s), w.sched_pairs, w.sched_len, kTMTok);
   }
 }
 
@@ -535,7 +535,7 @@ static meft_status route_impl(const meft_shape& s, const void* h, const void* Wg
     n_part = kt % 4 == 0 ? 4 : (kt % 2 == 0 ? 2 : 1);
     ProbRouter pr{static_cast<const uint16_t*>(h), static_cast<const uint16_t*>(Wg), p, s.T, s.d, s.n_blocks, n_part};
     set_gemm_extents(pr, (uint64_t)s.T * s.d * 2, (uint64_t)s.n_blocks * s.d * 2);
-    launch_gemm_mfma("router_gemm", pr, n_part * ((s.T + kTM - 1) / kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
+    launch_gemm_mfma("router_gemm", pr, n_part * ((s.T + ProbRouter::kTM - 1) / ProbRouter::kTM) * ((s.n_blocks + kTN - 1) / kTN), st);
   } else {
     GemmNTArgs a{};
     a.A = h; a.Bm = Wg; a.C = p; a.perm = nullptr; a.group_off = nullptr; a.tile_off = nullptr;
@@ -636,29 +636,38 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     const int bsp = round64(s.block_size);
     const uint16_t *hh = static_cast<const uint16_t*>(h), *kk = static_cast<const uint16_t*>(K),
                    *vv = static_cast<const uint16_t*>(V), *gg = static_cast<const uint16_t*>(dOut);
-    MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
-                st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
-    launch_dispatch(s, w, kGemmBM, true, true, st);
+    // With MEFT_FLAG_REUSE_FWD the dispatch tables and the activation rows A' are the ones the forward of this step
+    // left in the workspace; otherwise they are rebuilt from (idx, act).
+    const bool reuse = (s.flags & MEFT_FLAG_REUSE_FWD) != 0;
+    if (!reuse) {
+      MEFT_LAUNCH("blocks_from_idx", blocks_from_idx_kernel, dim3(s.T), dim3(64), (size_t)((s.n_blocks + 31) / 32) * 4,
+                  st, idx, s.top_k, s.N, s.block_size, s.n_blocks, s.top_e, w.sblk);
+      launch_dispatch(s, w, kGemmBM, true, true, st);
+    }
     // the flags and the row of zeros start from zero (adjacent in the workspace); 4-byte fill
     const size_t clear_words = (size_t)(reinterpret_cast<char*>(w.Ap) - reinterpret_cast<char*>(w.flag)) / 4;
     MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((unsigned)((clear_words + 255) / 256)), dim3(256), 0, st, w.flag,
                 clear_words, 0);
-    // a token's rows take top_e * bsp * 2 bytes of LDS: up to 96 KB where blocks are small and many (the default
-    // limit of a launch is 64 KB)
-    static std::once_flag act_rows_configured;
-    std::call_once(act_rows_configured, [] {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&act_rows_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kMaxLdsC * 2);
-    });
-    MEFT_LAUNCH("act_rows", act_rows_kernel, dim3(s.T), dim3(256), (size_t)s.top_e * bsp * 2, st, idx, act, s.top_k,
-                s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.Ap, w.flag);
+    if (reuse) {
+      MEFT_LAUNCH("mark_idx", mark_idx_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.flag);
+    } else {
+      // a token's rows take top_e * bsp * 2 bytes of LDS: up to 96 KB where blocks are small and many (the default
+      // limit of a launch is 64 KB)
+      static std::once_flag act_rows_configured;
+      std::call_once(act_rows_configured, [] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&act_rows_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kMaxLdsC * 2);
+      });
+      MEFT_LAUNCH("act_rows", act_rows_kernel, dim3(s.T), dim3(256), (size_t)s.top_e * bsp * 2, st, idx, act, s.top_k,
+                  s.N, s.block_size, bsp, s.top_e, w.sblk, w.slot_of_ent, w.Ap, w.flag);
+    }
     const int n_chunks = (s.N + kFlagChunk - 1) / kFlagChunk;
     MEFT_LAUNCH("count_flags", count_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt);
     MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
                 touched, n_touched);
     const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
     // every listed group has the same tiles; in the worst case one XCD holds all groups
-    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
+    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTMNeu - 1) / kTMNeu) * ((s.d + kTN - 1) / kTN);
     const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
     ProbNeuTN pn{};
     pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
@@ -719,7 +728,7 @@ static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& 
   MEFT_LAUNCH("union_maps", union_maps_kernel, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, n_S, g.cap,
               s.T, g.vbs, g.nvb, w.sblk, w.perm, w.tok_of_slot, w.slot_of_ent, w.group_off, w.rowflag);
   MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, g.nvb, sched_cap(g.vs),
-              w.sched_pairs, w.sched_len);
+              w.sched_pairs, w.sched_len, kTMTok);
   // the row of zeros that pads the contraction over tokens in the weight-gradient GEMMs (vbs % 64 == 0)
   MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((g.vbs / 2 + 255) / 256), dim3(256), 0, st,
               reinterpret_cast<int32_t*>(w.zrow), (size_t)g.vbs / 2, 0);
@@ -817,7 +826,7 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
     launch_gemm_mfma("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(g.vs, w.part, w, dh, st);
   }
-  const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTM - 1) / kTM) * ((s.d + kTN - 1) / kTN);
+  const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTMNeu - 1) / kTMNeu) * ((s.d + kTN - 1) / kTN);
   const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
   ProbNeuTN pn{};
   pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;

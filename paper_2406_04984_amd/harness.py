@@ -56,7 +56,8 @@ class DeviceLayer:
         self.cfg = c
         self.shape = binding.make_shape(c.T, c.d, c.n_blocks, c.block_size, c.top_e, c.top_k, c.dtype,
                                         flags=(binding.MEFT_FLAG_HOST_KV if c.host_kv else 0) |
-                                              (binding.MEFT_FLAG_KEEP_STAGED if c.host_kv and c.keep_staged else 0))
+                                              (binding.MEFT_FLAG_KEEP_STAGED if c.host_kv and c.keep_staged else 0) |
+                                              (binding.MEFT_FLAG_REUSE_FWD if c.reuse_fwd else 0))
         self.dt = torch.bfloat16 if c.dtype == "bf16" else torch.float32
         dev = "cuda"
         self.h, self.Wg, self.dOut = (to_device(t, n) for n in ("h", "Wg", "dOut"))

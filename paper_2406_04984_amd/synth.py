@@ -48,6 +48,7 @@ class Config:
     zipf_s: float = 0.0         # >0: router bias -s*ln(rank), rank a seeded permutation
     host_kv: bool = False       # K, V (and dK, dV) live in pinned host memory
     keep_staged: bool = False   # with host_kv: the backward reuses the device copies the forward staged
+    reuse_fwd: bool = False     # the backward takes the forward's entry grouping and activation rows from the workspace
     seed: int = BASE_SEED
 
     @property
@@ -65,17 +66,17 @@ class Config:
 CONFIGS: Dict[str, Config] = {
     "tiny_f32": Config("tiny_f32", "f32", 256, 128, 16, 128, 2, 32, seed=BASE_SEED + 1),
     "small_bf16": Config("small_bf16", "bf16", 2048, 1024, 64, 256, 4, 128,
-                         outlier_frac=0.01, outlier_scale=8.0, seed=BASE_SEED + 2),
+                         outlier_frac=0.01, outlier_scale=8.0, reuse_fwd=True, seed=BASE_SEED + 2),
     "llama7b_bf16": Config("llama7b_bf16", "bf16", 8192, 4096, 64, 1024, 4, 256,
-                           outlier_frac=0.005, outlier_scale=10.0, seed=BASE_SEED + 3),
+                           outlier_frac=0.005, outlier_scale=10.0, reuse_fwd=True, seed=BASE_SEED + 3),
     # the paper's ablation without key experts (Section 4.3, "MEFT w/o KE"): one block holds every neuron
     "noke_bf16": Config("noke_bf16", "bf16", 2048, 4096, 1, 65536, 1, 256,
                         outlier_frac=0.005, outlier_scale=10.0, seed=BASE_SEED + 6),
     "wide_bf16": Config("wide_bf16", "bf16", 4096, 4096, 256, 1024, 8, 512,
-                        zipf_s=1.1, seed=BASE_SEED + 4),
+                        zipf_s=1.1, reuse_fwd=True, seed=BASE_SEED + 4),
     "llama7b_hostkv_bf16": Config("llama7b_hostkv_bf16", "bf16", 8192, 4096, 128, 1024, 4, 256,
                                   outlier_frac=0.005, outlier_scale=10.0, host_kv=True, keep_staged=True,
-                                  seed=BASE_SEED + 5),
+                                  reuse_fwd=True, seed=BASE_SEED + 5),
 }
 
 

@@ -44,7 +44,7 @@ def test_shape_validation(B):
     assert B.meft_check_shape(_shape(B)) == B.MEFT_OK
     assert B.meft_workspace_bytes(_shape(B)) >= 256
     bad = [dict(top_e=5), dict(top_e=0), dict(top_k=17), dict(top_k=0), dict(T=-1), dict(d=0),
-           dict(N=31), dict(dtype=7), dict(activation=1), dict(flags=2), dict(block_size=0)]
+           dict(N=31), dict(dtype=7), dict(activation=1), dict(flags=2), dict(flags=16), dict(block_size=0)]
     for kw in bad:
         s = _shape(B, **kw)
         assert B.meft_check_shape(s) == B.MEFT_ERR_INVALID_ARG, kw
@@ -96,7 +96,9 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(B):
     assert B.meft_check_shape(_shape(B, flags=B.MEFT_FLAG_HOST_KV | B.MEFT_FLAG_KEEP_STAGED)) == B.MEFT_OK
     assert B.meft_check_shape(_shape(B, flags=4)) == B.MEFT_ERR_INVALID_ARG       # needs MEFT_FLAG_HOST_KV
     assert B.meft_check_shape(_shape(B, flags=7)) == B.MEFT_OK
-    assert B.meft_check_shape(_shape(B, flags=9)) == B.MEFT_ERR_INVALID_ARG
+    assert B.meft_check_shape(_shape(B, flags=9)) == B.MEFT_OK            # host-resident + reuse of the forward's tables
+    assert B.meft_check_shape(_shape(B, flags=8)) == B.MEFT_OK
+    assert B.meft_check_shape(_shape(B, flags=17)) == B.MEFT_ERR_INVALID_ARG
     fake = 0x1000
     assert B._lib.meft_hostkv_stage(ctypes.byref(_shape(B)), fake, fake, fake, fake, 1 << 30, None) == B.MEFT_ERR_INVALID_ARG
     # the host-resident variant needs room for device copies of K, V and staging for dK, dV

@@ -121,3 +121,36 @@ def test_measurement_probes_run():
     torch.cuda.synchronize()
     assert torch.equal(a, b)
     assert bool(torch.isfinite(out).all()) and bool((out != 0).any())
+
+
+@pytest.mark.parametrize("kw", CASES + [dict(T=333, d=192, n_blocks=5, block_size=72, top_e=2, top_k=19, dtype="bf16",
+                                             seed=1104),
+                                        dict(T=200, d=128, n_blocks=12, block_size=64, top_e=8, top_k=70, dtype="bf16",
+                                             seed=1105)],
+                         ids=["gather_f32", "dense_bf16", "dense_ragged", "dense_top_e_8"])
+def test_backward_on_the_forwards_tables_gives_the_same_bits(kw):
+    """MEFT_FLAG_REUSE_FWD: the backward takes the grouping of the entries and the activation rows from the
+    workspace, where the forward of the step left them, instead of rebuilding both from (idx, act).  Two steps in
+    a row, each bit-identical to the plain run; the per-pair formulation ignores the flag."""
+    t = synth.make_inputs(synth.small_case(**kw))
+    ref = P.run_gpu(t)
+    tr = synth.Tensors(t.cfg.replace(reuse_fwd=True), t.h, t.Wg, t.K, t.V, t.dOut, t.bias, t.outlier_channels)
+    layer = P.DeviceLayer(tr)
+    for _ in range(2):
+        layer.fill_grad_sentinel()
+        layer.ws.fill_(0xFF)
+        layer.step()
+        _same(ref, layer.results())
+
+
+def test_backward_on_the_forwards_tables_when_a_routed_block_gives_no_neuron():
+    """A token routed to a block none of whose neurons makes its top-k: the forward's grouping holds an entry that a
+    grouping rebuilt from idx does not have; its activation row is all zero and changes no result."""
+    cfg = synth.small_case(T=120, d=128, n_blocks=6, block_size=64, top_e=3, top_k=20, dtype="bf16", seed=1106)
+    t = synth.make_inputs(cfg)
+    t.K[3 * 64:4 * 64] *= 1e-3            # block 3's scores are tiny: routed to, never selected from
+    t.bias = np.array([0, 0, 0, 50, 0, 0], np.float32)
+    ref = P.run_gpu(t)
+    assert (ref["block_idx"] == 3).any(axis=1).all() and not ((ref["idx"] >= 192) & (ref["idx"] < 256)).any()
+    tr = synth.Tensors(cfg.replace(reuse_fwd=True), t.h, t.Wg, t.K, t.V, t.dOut, t.bias, t.outlier_channels)
+    _same(ref, P.run_gpu(tr))
