@@ -204,15 +204,20 @@ struct FwdWs : DenseWs {
   }
 };
 
+// upper bound of the chunks of neurons with more than one chunk: such a neuron has more than kSegChunk pairs, so its
+// ceil(L / kSegChunk) chunks are fewer than 2 L / kSegChunk
+size_t seg_multi_chunks(const meft_shape& s) { return 2 * (((size_t)s.T * s.top_k) / kSegChunk) + 1; }
+
 struct BwdWs : DenseWs {
   // gather path
   float* ds;
-  int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted;
+  int32_t *cnt_n, *cursor, *seg_off, *pair_list, *pair_sorted, *work_off, *multi_off;
+  float* seg_part;   // fp32 chunk sums of the neurons with more than kSegChunk pairs: [chunk][dV | dK][d]
   size_t bytes;
   BwdWs(const meft_shape& s, void* ws) {
     Carver c(ws);
     const size_t P = (size_t)s.T * s.top_k;
-    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = nullptr;
+    ds = nullptr; cnt_n = cursor = seg_off = pair_list = pair_sorted = work_off = multi_off = nullptr; seg_part = nullptr;
     if (use_dense(s)) {
       carve_dense(s, c);
     } else {
@@ -222,6 +227,10 @@ struct BwdWs : DenseWs {
       seg_off = c.take<int32_t>((size_t)s.N + 1);
       pair_list = c.take<int32_t>(P);
       pair_sorted = c.take<int32_t>(P);
+      const size_t n_seg = (size_t)s.N < P ? (size_t)s.N : P;
+      work_off = c.take<int32_t>(n_seg + 1);
+      multi_off = c.take<int32_t>(n_seg + 1);
+      seg_part = c.take<float>(seg_multi_chunks(s) * 2 * (size_t)s.d);
     }
     bytes = c.off;
   }
@@ -437,7 +446,16 @@ void launch_seg_reduce(const meft_shape& s, const BwdWs& w, const int32_t* touch
   row_launch(s.d, nthr, nv);
   const T *hh = static_cast<const T*>(h), *g = static_cast<const T*>(dOut);
   T *pk = static_cast<T*>(dK), *pv = static_cast<T*>(dV);
-#define SR(NV) MEFT_LAUNCH("seg_reduce", (seg_reduce_kernel<T, NV>), dim3(grid), dim3(nthr), 0, st, touched, n_touched, w.seg_off, w.pair_sorted, act, w.ds, hh, g, s.d, s.top_k, pk, pv)
+  // one workgroup per chunk: at most one chunk per touched neuron plus one per kSegChunk pairs
+  const int64_t work = (int64_t)grid + ((int64_t)s.T * s.top_k) / kSegChunk;
+  const int finish = grid < 4096 ? grid : 4096;
+#define SR(NV)                                                                                                        \
+  do {                                                                                                                \
+    MEFT_LAUNCH("seg_reduce", (seg_reduce_kernel<T, NV>), dim3((unsigned)work), dim3(nthr), 0, st, touched, n_touched, \
+                w.seg_off, w.work_off, w.multi_off, w.pair_sorted, act, w.ds, hh, g, s.d, s.top_k, pk, pv, w.seg_part); \
+    MEFT_LAUNCH("seg_finish", (seg_finish_kernel<T, NV>), dim3(finish), dim3(nthr), 0, st, touched, n_touched,        \
+                w.work_off, w.multi_off, w.seg_part, s.d, pk, pv);                                                     \
+  } while (0)
   switch (nv) { case 1: SR(1); break; case 2: SR(2); break; case 4: SR(4); break; default: SR(8); }
 #undef SR
 }
@@ -708,7 +726,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
               n_clear, 0);
   MEFT_LAUNCH("pair_count", pair_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.cnt_n);
   MEFT_LAUNCH("pair_scan", pair_scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt_n, s.N, w.seg_off, touched,
-              n_touched);
+              n_touched, w.work_off, w.multi_off);
   MEFT_LAUNCH("pair_fill", pair_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, idx, P, s.N, w.seg_off,
               w.cursor, w.pair_list);
   const int n_seg = s.N < P ? s.N : P;  // upper bound on the number of touched neurons

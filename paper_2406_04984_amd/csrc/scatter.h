@@ -1,7 +1,8 @@
 // Backward weight gradients without floating-point atomics: the (token, neuron) pairs are grouped
 // by neuron (counting sort; integer atomics only decide positions, and every group is then put in
-// ascending pair order, i.e. ascending token), and one workgroup per touched neuron sums its
-// group in that fixed order:  dV[j,:] = sum act * dOut[t,:],  dK[j,:] = sum ds * h[t,:].
+// ascending pair order, i.e. ascending token), and the group is summed in that fixed order, in chunks of
+// kSegChunk pairs (one workgroup each; the chunk sums of a long group are added in chunk order):
+//   dV[j,:] = sum act * dOut[t,:],  dK[j,:] = sum ds * h[t,:].
 // Only touched rows are written.
 #pragma once
 #include "common.h"
@@ -85,14 +86,22 @@ __global__ void pair_count_kernel(const int32_t* __restrict__ idx, int P, int N,
   if (p < P) atomicAdd(&cnt[clampi(idx[p], 0, N - 1)], 1);
 }
 
-// seg_off = exclusive scan of cnt; touched = ascending ids with cnt > 0.  One workgroup of 1024; thread t owns a
-// run of consecutive counters (a multiple of 4, so that its 16-byte loads and stores are aligned) and reads them
-// sixteen at a time with independent loads: read one by one, each counter costs a trip to memory.
+// A neuron's pairs are summed in chunks of kSegChunk consecutive pairs, one workgroup per chunk, so that a neuron that
+// very many tokens selected does not leave one workgroup with all of its pairs.
+constexpr int kSegChunk = 256;
+
+// seg_off = exclusive scan of cnt; touched = ascending ids with cnt > 0; and per touched neuron u (in that order)
+// work_off[u] = chunks of the touched neurons before it, multi_off[u] = the same counting only neurons of more than
+// one chunk (their chunks leave partial sums in a buffer); entry [*n_touched] of both holds the total.  One workgroup
+// of 1024; thread t owns a run of consecutive counters (a multiple of 4, so that its 16-byte loads and stores are
+// aligned) and reads them sixteen at a time with independent loads: read one by one, each counter costs a trip to memory.
 __global__ __launch_bounds__(1024) void pair_scan_kernel(const int32_t* __restrict__ cnt, int N,
                                                          int32_t* __restrict__ seg_off,
                                                          int32_t* __restrict__ touched,
-                                                         int32_t* __restrict__ n_touched) {
-  __shared__ int s_c[16], s_f[16];
+                                                         int32_t* __restrict__ n_touched,
+                                                         int32_t* __restrict__ work_off,
+                                                         int32_t* __restrict__ multi_off) {
+  __shared__ int s_c[16], s_f[16], s_w[16], s_m[16];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int chunk = ((N + 1023) / 1024 + 3) & ~3;
   const int j0 = min(N, tid * chunk), j1 = min(N, j0 + chunk);
@@ -108,19 +117,23 @@ __global__ __launch_bounds__(1024) void pair_scan_kernel(const int32_t* __restri
       for (int q = 0; q < 16; ++q) v[q] = j + q < j1 ? cnt[j + q] : 0;
     }
   };
-  int c = 0, f = 0;
+  auto chunks_of = [](int v) { return (v + kSegChunk - 1) / kSegChunk; };
+  int c = 0, f = 0, wk = 0, mu = 0;
   for (int j = j0; j < j1; j += 16) {
     int v[16];
     load16(j, v);
 #pragma unroll
-    for (int q = 0; q < 16; ++q) { c += v[q]; f += v[q] > 0; }
+    for (int q = 0; q < 16; ++q) {
+      const int ch = chunks_of(v[q]);
+      c += v[q]; f += v[q] > 0; wk += ch; mu += ch > 1 ? ch : 0;
+    }
   }
-  const int ci = wave_incl_scan(c), fi = wave_incl_scan(f);
-  if (lane == 63) { s_c[w] = ci; s_f[w] = fi; }
+  const int ci = wave_incl_scan(c), fi = wave_incl_scan(f), wi = wave_incl_scan(wk), mi = wave_incl_scan(mu);
+  if (lane == 63) { s_c[w] = ci; s_f[w] = fi; s_w[w] = wi; s_m[w] = mi; }
   __syncthreads();
-  int cb = 0, fb = 0;
-  for (int i = 0; i < w; ++i) { cb += s_c[i]; fb += s_f[i]; }
-  int off = cb + ci - c, nt = fb + fi - f;
+  int cb = 0, fb = 0, wb = 0, mb = 0;
+  for (int i = 0; i < w; ++i) { cb += s_c[i]; fb += s_f[i]; wb += s_w[i]; mb += s_m[i]; }
+  int off = cb + ci - c, nt = fb + fi - f, wo = wb + wi - wk, mo = mb + mi - mu;
   for (int j = j0; j < j1; j += 16) {
     int v[16], o[16];
     load16(j, v);
@@ -137,9 +150,15 @@ __global__ __launch_bounds__(1024) void pair_scan_kernel(const int32_t* __restri
     }
 #pragma unroll
     for (int q = 0; q < 16; ++q)
-      if (v[q] > 0) touched[nt++] = j + q;   // (v[q] is 0 beyond the run)
+      if (v[q] > 0) {   // (v[q] is 0 beyond the run)
+        const int ch = chunks_of(v[q]);
+        touched[nt] = j + q;
+        work_off[nt] = wo;
+        multi_off[nt] = mo;
+        ++nt; wo += ch; mo += ch > 1 ? ch : 0;
+      }
   }
-  if (tid == 1023) { seg_off[N] = off; *n_touched = nt; }
+  if (tid == 1023) { seg_off[N] = off; *n_touched = nt; work_off[nt] = wo; multi_off[nt] = mo; }
 }
 
 // unordered placement of the pairs into their neuron's segment
@@ -153,21 +172,23 @@ __global__ void pair_fill_kernel(const int32_t* __restrict__ idx, int P, int N,
   pair_list[seg_off[j] + pos] = p;
 }
 
-// puts every segment in ascending pair order: rank of an entry = number of smaller entries of the
-// segment (pair ids are distinct).  One workgroup per touched neuron.
+// puts every segment in ascending pair order (pair ids are distinct).  One workgroup per touched neuron.  Up to
+// kRankMax entries: rank of an entry = number of smaller entries of the segment.  Up to kBitonicMax: a bitonic sort
+// in LDS (a neuron that thousands of tokens selected would cost L^2 comparisons otherwise).  Beyond that (more tokens
+// than kBitonicMax selected one neuron): ranks counted against global memory, slow but never wrong.
 __global__ __launch_bounds__(256) void seg_sort_kernel(const int32_t* __restrict__ touched,
                                                        const int32_t* __restrict__ n_touched,
                                                        const int32_t* __restrict__ seg_off,
                                                        const int32_t* __restrict__ pair_list,
                                                        int32_t* __restrict__ pair_sorted) {
-  constexpr int LMAX = 2048;
-  __shared__ int32_t s_p[LMAX];
+  constexpr int kRankMax = 256, kBitonicMax = 8192;
+  __shared__ int32_t s_p[kBitonicMax];
   const int u = blockIdx.x;
   if (u >= *n_touched) return;
   const int j = touched[u];
   const int o = seg_off[j], L = seg_off[j + 1] - o;
   const int32_t* src = pair_list + o;
-  if (L <= LMAX) {
+  if (L <= kRankMax) {
     for (int i = threadIdx.x; i < L; i += 256) s_p[i] = src[i];
     __syncthreads();
     for (int i = threadIdx.x; i < L; i += 256) {
@@ -176,6 +197,22 @@ __global__ __launch_bounds__(256) void seg_sort_kernel(const int32_t* __restrict
       for (int z = 0; z < L; ++z) r += s_p[z] < v;
       pair_sorted[o + r] = v;
     }
+  } else if (L <= kBitonicMax) {
+    int n = 512;
+    while (n < L) n <<= 1;
+    for (int i = threadIdx.x; i < n; i += 256) s_p[i] = i < L ? src[i] : 0x7FFFFFFF;   // padding sorts to the end
+    __syncthreads();
+    for (int size = 2; size <= n; size <<= 1)
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        for (int i = threadIdx.x; i < n / 2; i += 256) {
+          const int lo = ((i / stride) * stride * 2) + (i % stride), hi = lo + stride;
+          const bool up = (lo & size) == 0;   // ascending half of this merge
+          const int a = s_p[lo], b = s_p[hi];
+          if ((a > b) == up) { s_p[lo] = b; s_p[hi] = a; }
+        }
+        __syncthreads();
+      }
+    for (int i = threadIdx.x; i < L; i += 256) pair_sorted[o + i] = s_p[i];
   } else {
     for (int i = threadIdx.x; i < L; i += 256) {
       const int v = src[i];
@@ -186,27 +223,40 @@ __global__ __launch_bounds__(256) void seg_sort_kernel(const int32_t* __restrict
   }
 }
 
-// dV[j,:] and dK[j,:] of one touched neuron, pairs summed in ascending pair order.
+// One chunk of a touched neuron's pairs (kSegChunk consecutive pairs of its segment, summed in ascending pair order):
+// workgroup w takes chunk number w of the list that work_off describes.  A neuron of one chunk gets its rows dV[j,:],
+// dK[j,:] written here; the chunks of a longer segment leave their fp32 sums in `part` ([chunk][dV | dK][d], chunks
+// numbered by multi_off), which seg_finish_kernel adds in chunk order.
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(const int32_t* __restrict__ touched,
                                                          const int32_t* __restrict__ n_touched,
                                                          const int32_t* __restrict__ seg_off,
+                                                         const int32_t* __restrict__ work_off,
+                                                         const int32_t* __restrict__ multi_off,
                                                          const int32_t* __restrict__ pair_sorted,
                                                          const float* __restrict__ act,
                                                          const float* __restrict__ ds,
                                                          const T* __restrict__ h, const T* __restrict__ dOut,
                                                          int d, int k, T* __restrict__ dK,
-                                                         T* __restrict__ dV) {
-  const int u = blockIdx.x;
-  if (u >= *n_touched) return;
+                                                         T* __restrict__ dV, float* __restrict__ part) {
+  const int nt = *n_touched;
+  const int wk = blockIdx.x;
+  if (wk >= work_off[nt]) return;
+  int lo = 0, hi = nt;   // work_off[lo] <= wk < work_off[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (work_off[mid] <= wk) lo = mid; else hi = mid;
+  }
+  const int u = lo, c = wk - work_off[u], nch = work_off[u + 1] - work_off[u];
   const int j = touched[u];
-  const int o = seg_off[j], L = seg_off[j + 1] - o;
+  const int o = seg_off[j] + c * kSegChunk;
+  const int L = min(seg_off[j + 1] - o, kSegChunk);
   const int tid = threadIdx.x, nthr = blockDim.x;
   float aK[NV][8], aV[NV][8];
 #pragma unroll
   for (int v = 0; v < NV; ++v)
 #pragma unroll
-    for (int c = 0; c < 8; ++c) { aK[v][c] = 0.f; aV[v][c] = 0.f; }
+    for (int cc = 0; cc < 8; ++cc) { aK[v][cc] = 0.f; aV[v][cc] = 0.f; }
   constexpr int U = 2;
   int q = 0;
   for (; q + U <= L; q += U) {
@@ -231,9 +281,9 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(const int32_t* __restri
 #pragma unroll
       for (int v = 0; v < NV; ++v)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          aV[v][c] = fmaf(a[z], xg[z][v][c], aV[v][c]);
-          aK[v][c] = fmaf(s[z], xh[z][v][c], aK[v][c]);
+        for (int cc = 0; cc < 8; ++cc) {
+          aV[v][cc] = fmaf(a[z], xg[z][v][cc], aV[v][cc]);
+          aK[v][cc] = fmaf(s[z], xh[z][v][cc], aK[v][cc]);
         }
   }
   for (; q < L; ++q) {
@@ -248,19 +298,75 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(const int32_t* __restri
         Vec8<T>::load(dOut + (size_t)t * d + col, xg);
         Vec8<T>::load(h + (size_t)t * d + col, xh);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          aV[v][c] = fmaf(a, xg[c], aV[v][c]);
-          aK[v][c] = fmaf(s, xh[c], aK[v][c]);
+        for (int cc = 0; cc < 8; ++cc) {
+          aV[v][cc] = fmaf(a, xg[cc], aV[v][cc]);
+          aK[v][cc] = fmaf(s, xh[cc], aK[v][cc]);
         }
       }
     }
   }
+  if (nch == 1) {
 #pragma unroll
-  for (int v = 0; v < NV; ++v) {
-    const int col = (tid + v * nthr) * 8;
-    if (col < d) {
-      Vec8<T>::store(dV + (size_t)j * d + col, aV[v]);
-      Vec8<T>::store(dK + (size_t)j * d + col, aK[v]);
+    for (int v = 0; v < NV; ++v) {
+      const int col = (tid + v * nthr) * 8;
+      if (col < d) {
+        Vec8<T>::store(dV + (size_t)j * d + col, aV[v]);
+        Vec8<T>::store(dK + (size_t)j * d + col, aK[v]);
+      }
+    }
+  } else {
+    float* pv = part + (size_t)(multi_off[u] + c) * 2 * d;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int col = (tid + v * nthr) * 8;
+      if (col < d) {
+        Vec8<float>::store(pv + col, aV[v]);
+        Vec8<float>::store(pv + d + col, aK[v]);
+      }
+    }
+  }
+}
+
+// The rows of the touched neurons of more than one chunk: their chunks' partial sums added in chunk order.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void seg_finish_kernel(const int32_t* __restrict__ touched,
+                                                         const int32_t* __restrict__ n_touched,
+                                                         const int32_t* __restrict__ work_off,
+                                                         const int32_t* __restrict__ multi_off,
+                                                         const float* __restrict__ part, int d,
+                                                         T* __restrict__ dK, T* __restrict__ dV) {
+  const int nt = *n_touched;
+  for (int u = blockIdx.x; u < nt; u += gridDim.x) {
+    const int nch = work_off[u + 1] - work_off[u];
+    if (nch <= 1) continue;
+    const int j = touched[u];
+    const float* pv = part + (size_t)multi_off[u] * 2 * d;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    float aK[NV][8], aV[NV][8];
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+      for (int cc = 0; cc < 8; ++cc) { aK[v][cc] = 0.f; aV[v][cc] = 0.f; }
+    for (int c = 0; c < nch; ++c) {
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int col = (tid + v * nthr) * 8;
+        if (col < d) {
+          float xv[8], xk[8];
+          Vec8<float>::load(pv + (size_t)c * 2 * d + col, xv);
+          Vec8<float>::load(pv + (size_t)c * 2 * d + d + col, xk);
+#pragma unroll
+          for (int cc = 0; cc < 8; ++cc) { aV[v][cc] += xv[cc]; aK[v][cc] += xk[cc]; }
+        }
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int col = (tid + v * nthr) * 8;
+      if (col < d) {
+        Vec8<T>::store(dV + (size_t)j * d + col, aV[v]);
+        Vec8<T>::store(dK + (size_t)j * d + col, aK[v]);
+      }
     }
   }
 }
