@@ -243,7 +243,8 @@ def main() -> int:
     del pm
 
     models = kernel_models(cfg, n_touched)
-    dominant = max((k for k in per_step if k in models), key=lambda k: per_step[k])
+    priced = [k for k in per_step if k in models and (models[k]["bytes"] if models[k]["bound"] == "hbm" else models[k]["flop"])]
+    dominant = max(priced, key=lambda k: per_step[k])
     m = models[dominant]
     dur_s = kern[dominant] * 1e-3
     if m["bound"] == "hbm":
@@ -413,7 +414,7 @@ def main() -> int:
             l2 = DeviceLayer(t2, B)
             ms2, kern2, per2 = time_layer(l2, B, max(5, args.steps // 2), max(3, args.warmup // 2))
             mod2 = kernel_models(c2, int(l2.n_touched.item()))
-            dom2 = max((k for k in per2 if k in mod2), key=lambda k: per2[k])
+            dom2 = max((k for k in per2 if k in mod2 and (mod2[k]["bytes"] or mod2[k]["flop"])), key=lambda k: per2[k])
             entry = {"ms_per_step": round(ms2, 4), "tokens/s": round(c2.T / (ms2 * 1e-3), 1),
                      "dominant_kernel": dom2, "dominant": price(c2, mod2, dom2, kern2[dom2]),
                      "whole_step_frac_hbm_compulsory": round(mod2["_step"]["bytes"] / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
