@@ -86,6 +86,7 @@ struct ProbTokKC {
   const uint16_t* W;          // K or V, [N, d]
   const int32_t* perm; const int32_t* group_off;
   TokenSched sched;
+  int big_only;               // 1: the groups of at most small_rows tokens are left to the per-pair kernels
   int e, bs, bsp, d;
   float* sc;                  // kTokScores: [T*e, bs]
   const uint16_t* Ap;         // kTokMasked: A' [slots, bsp]
@@ -95,7 +96,8 @@ struct ProbTokKC {
   __device__ const uint16_t* b_base() const { return W; }
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
-    if (!locate_token_tile(sched, group_off, wg, (bs + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
+    if (!locate_token_tile(sched, group_off, wg, (bs + kTN - 1) / kTN, big_only != 0, tc.g, mt, nt, tc.slot0, rows))
+      return false;
     tc.m0 = mt * kTM; tc.n0 = nt * kTN; tc.Mrows = rows; tc.Ncols = bs; tc.nk = d / kTK;
     return true;
   }
@@ -161,6 +163,7 @@ struct ProbTokNC {
   const uint16_t* W;          // V or K, [N, d]
   const int32_t* group_off;
   TokenSched sched;
+  int big_only;               // 1: the groups of at most small_rows tokens are left to the per-pair kernels
   int bs, bsp, d;
   uint16_t* part;             // [slots, d] bf16: one block's contribution to a token's row
   uint32_t a_bytes, b_bytes; bool buf;
@@ -168,7 +171,8 @@ struct ProbTokNC {
   __device__ const uint16_t* b_base() const { return W; }
   __device__ bool locate(int wg, TileCoord& tc) const {
     int mt, nt, rows;
-    if (!locate_token_tile(sched, group_off, wg, (d + kTN - 1) / kTN, tc.g, mt, nt, tc.slot0, rows)) return false;
+    if (!locate_token_tile(sched, group_off, wg, (d + kTN - 1) / kTN, big_only != 0, tc.g, mt, nt, tc.slot0, rows))
+      return false;
     tc.m0 = mt * kTM; tc.n0 = nt * kTN; tc.Mrows = rows; tc.Ncols = d; tc.nk = bsp / kTK;
     return true;
   }
@@ -207,6 +211,7 @@ struct ProbNeuTN {
   const int32_t* group_off; const int32_t* tok_of_slot;
   const int32_t* flag;        // [N] > 0 where some token selected the neuron
   TokenSched sched;           // only the group lists are used: every group has the same number of tiles
+  int big_only;               // 1: the groups of at most small_rows tokens are left to the per-pair kernels
   int bs, bsp, d;
   uint16_t* G;                // dV or dK [N, d]
   uint32_t a_bytes, b_bytes; bool buf;
@@ -225,7 +230,7 @@ struct ProbNeuTN {
       gi = local / (tm * tn);
       w = local - gi * (tm * tn);
     }
-    if (gi >= as_const(sched.len)[x]) return false;
+    if (gi >= as_const(sched.len)[big_only ? kXcd + 1 + x : x]) return false;
     tc.g = as_const(sched.grp)[(size_t)x * sched.cap + gi].x;
     tc.slot0 = as_const(group_off)[tc.g];
     const int rows = as_const(group_off)[tc.g + 1] - tc.slot0;   // > 0: the lists hold non-empty groups only

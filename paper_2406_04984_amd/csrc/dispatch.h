@@ -12,6 +12,7 @@
 #pragma once
 #include "gemm_mfma.h"
 #include "select.h"
+#include "small_groups.h"
 
 namespace meft {
 
@@ -58,13 +59,16 @@ __global__ __launch_bounds__(1024) void dispatch_count_kernel(const int32_t* __r
 }
 
 // pass 2, one workgroup: H[chunk][b] becomes the number of entries of block b in the chunks before; cnt, group_off,
-// tile_off; with grp != nullptr also the tile schedule.
+// tile_off; with grp != nullptr also the tile schedule; with small_ent != nullptr the lists of the small groups.
 __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int32_t* __restrict__ H, int n_chunks, int n_blocks,
                                                              int BM, int32_t* __restrict__ cnt,
                                                              int32_t* __restrict__ group_off,
                                                              int32_t* __restrict__ tile_off, int cap,
                                                              int2* __restrict__ grp, int* __restrict__ len,
-                                                             int sched_tile_m) {
+                                                             int sched_tile_m, int small_rows,
+                                                             int2* __restrict__ small_ent,
+                                                             int32_t* __restrict__ small_grp,
+                                                             int32_t* __restrict__ small_cnt) {
   __shared__ int s_w[16];
   const int tid = threadIdx.x;   // = block, n_blocks <= 1024
   int tot = 0;
@@ -89,7 +93,11 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int32_t* __restrict
   if (tid == 0) { group_off[n_blocks] = all_g; tile_off[n_blocks] = all_t; }
   if (grp != nullptr) {
     __syncthreads();   // group_off is read back below
-    build_sched_body(group_off, n_blocks, cap, grp, len, sched_tile_m);
+    build_sched_body(group_off, n_blocks, cap, grp, len, sched_tile_m, small_rows);
+  }
+  if (small_ent != nullptr) {
+    __syncthreads();   // group_off is read back; s_w is free again
+    small_lists_body(group_off, n_blocks, small_rows, small_ent, small_grp, small_cnt, s_w);
   }
 }
 

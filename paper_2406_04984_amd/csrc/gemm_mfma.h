@@ -760,18 +760,25 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 // XCD with the least work so far (ties to the lower XCD); the work of a group is counted in 64-row units plus
 // a constant for the per-tile overhead, which balances both the token-major tile counts and the contraction
 // lengths of the neuron-major problems.  Which XCD computes a group has no influence on any result.
+//
+// Groups of at most `small_rows` tokens come last in every list (the deal runs from the longest group down), and a
+// second set of list lengths counts only the larger groups in front of them: a problem that leaves the small groups
+// to the per-pair kernels (small_groups.h) walks that prefix of the same lists.
 struct TokenSched {
   const int2* grp;       // [kXcd][cap]
-  const int* len;        // [kXcd] number of groups in the list; [kXcd]: 1 = every list holds every group (split)
+  const int* len;        // [kXcd] number of groups in the list; [kXcd]: 1 = every list holds every group (split);
+                         // [kXcd + 1 + x]: groups of more than small_rows tokens in XCD x's list (a prefix of it)
   int cap;               // entries per XCD (n_groups + 1)
   int max_tiles;         // upper bound of m tiles of one XCD (for the tile-id bound of a launch)
 };
+constexpr int kSchedLenInts = 2 * kXcd + 1;
 
 constexpr int kSchedSortMax = 1024;   // up to this many groups are dealt out longest first; more: round-robin
 
 // Executed by one whole workgroup of 1024 threads.
 __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ group_off, int n_groups, int cap,
-                                                 int2* __restrict__ grp, int* __restrict__ len, int tile_m) {
+                                                 int2* __restrict__ grp, int* __restrict__ len, int tile_m,
+                                                 int small_rows) {
   __shared__ int s_rows[kSchedSortMax];
   __shared__ int s_order[kSchedSortMax];
   __shared__ int s_sorted[kSchedSortMax];
@@ -798,13 +805,14 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
       // the deal itself is sequential; lanes 0..7 of the first wave each keep one XCD's work, list length and tile
       // count, and a three-step DPP butterfly finds the least loaded XCD (ties to the lower one)
       const int lane = tid;
-      int load = 0, n = 0, tiles = 0;
+      int load = 0, n = 0, tiles = 0, n_big = 0;
       for (int i = 0; i < n_full; ++i) {   // descending order: the non-empty groups come first
         const int g = s_order[i], r = s_sorted[i];
         if (split) {
           if (lane < kXcd) {
             grp[(size_t)lane * cap + n] = make_int2(g, tiles);
             n += 1;
+            n_big += r > small_rows ? 1 : 0;
             tiles += (r + tile_m - 1) / tile_m;
           }
           continue;
@@ -816,6 +824,7 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
         if (lane == (key & (kXcd - 1))) {   // true in one of the lanes 0..7 only: the higher lanes hold 0x7FFFFFFF
           grp[(size_t)lane * cap + n] = make_int2(g, tiles);
           n += 1;
+          n_big += r > small_rows ? 1 : 0;
           tiles += (r + tile_m - 1) / tile_m;
           load += (r + 63) / 64 + 2;
         }
@@ -823,6 +832,7 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
       if (lane < kXcd) {
         grp[(size_t)lane * cap + n] = make_int2(-1, tiles);
         len[lane] = n;
+        len[kXcd + 1 + lane] = n_big;
       }
     }
   } else if (tid < kXcd) {
@@ -837,19 +847,22 @@ __device__ __forceinline__ void build_sched_body(const int32_t* __restrict__ gro
     }
     grp[(size_t)x * cap + n] = make_int2(-1, tiles);
     len[x] = n;
+    len[kXcd + 1 + x] = n;   // unsorted lists: no group counts as small (the host passes small_rows = 0 here)
   }
 }
 
 __global__ __launch_bounds__(1024) void build_sched_kernel(const int32_t* __restrict__ group_off, int n_groups,
                                                            int cap, int2* __restrict__ grp, int* __restrict__ len,
-                                                           int tile_m) {
-  build_sched_body(group_off, n_groups, cap, grp, len, tile_m);
+                                                           int tile_m, int small_rows) {
+  build_sched_body(group_off, n_groups, cap, grp, len, tile_m, small_rows);
 }
 
+// big_only: walk only the groups of more than small_rows tokens (the prefix of every list that the second set of
+// lengths describes)
 __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int32_t* group_off, int wg, int tn,
-                                                   int& g, int& mt, int& nt, int& slot0, int& rows) {
+                                                   bool big_only, int& g, int& mt, int& nt, int& slot0, int& rows) {
   const int x = wg & (kXcd - 1), local = wg >> 3;
-  const int n = as_const(s.len)[x];
+  const int n = as_const(s.len)[big_only ? kXcd + 1 + x : x];
   const auto* list = as_const(s.grp) + (size_t)x * s.cap;
   if (as_const(s.len)[kXcd] != 0) {
     // split lists (fewer than 8 entries): XCD x takes the tiles x, x + 8, ... of every group, m tiles fastest
@@ -870,7 +883,7 @@ __device__ __forceinline__ bool locate_token_tile(const TokenSched& s, const int
     }
     return false;
   }
-  if (local >= list[n].y * tn) return false;
+  if (n == 0 || local >= list[n].y * tn) return false;
   int lo = 0, hi = n;  // list[lo].y * tn <= local < list[hi].y * tn
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;

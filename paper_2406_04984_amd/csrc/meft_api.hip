@@ -21,6 +21,7 @@
 #include "gemm_nt.h"
 #include "scatter.h"
 #include "select.h"
+#include "small_groups.h"
 #include "union_path.h"
 
 // Device memory of meft_route_static: part of the library's image, one copy on every GPU the library runs on.  In
@@ -124,6 +125,15 @@ bool use_dense(const meft_shape& s) {
 }
 
 int round64(int v) { return (v + 63) & ~63; }
+// Block-dense path: groups of at most this many tokens go to the per-pair kernels of small_groups.h (0: none).  The
+// tile schedule knows the small groups only where it deals the groups out longest first.
+// A contraction reads all block_size rows of the block for a group, the per-pair kernels about top_k / top_e rows for
+// each of its tokens: at top_e * block_size / top_k tokens both move the same bytes, so the limit is no larger.
+int small_rows_of(const meft_shape& s) {
+  if (!use_dense(s) || s.n_blocks > kSchedSortMax) return 0;
+  const int64_t even = (int64_t)s.top_e * s.block_size / s.top_k;   // >= 1: top_k <= top_e * block_size
+  return (int)(even < kSmallRows ? even : kSmallRows);
+}
 // per XCD: at most n_blocks groups (+1 end entry) and, as a bound that needs no knowledge of the deal, all m tiles
 int sched_cap(const meft_shape& s) { return s.n_blocks + 1; }
 int sched_max_tiles(const meft_shape& s) { return (int)(((int64_t)s.T * s.top_e) / kTMTok + s.n_blocks); }
@@ -157,6 +167,9 @@ struct DispatchWs {
   int32_t *sblk = nullptr, *cnt = nullptr, *group_off = nullptr, *tile_off = nullptr, *perm = nullptr,
           *tok_of_slot = nullptr, *slot_of_ent = nullptr, *sched_len = nullptr;
   int2* sched_pairs = nullptr;
+  // the groups of at most small_rows_of(s) tokens and their entries (small_groups.h), and the two list lengths
+  int2* small_ent = nullptr;
+  int32_t *small_grp = nullptr, *small_cnt = nullptr;
   void carve(const meft_shape& s, Carver& c) {
     const size_t n_ent = (size_t)s.T * s.top_e;
     sblk = c.take<int32_t>(n_ent);
@@ -166,9 +179,13 @@ struct DispatchWs {
     perm = c.take<int32_t>(n_ent);
     tok_of_slot = c.take<int32_t>(n_ent + kSlotPad);   // padded: see kSlotPad
     slot_of_ent = c.take<int32_t>(n_ent);
-    sched_len = c.take<int32_t>(kXcd + 1);   // one list length per XCD, then the split flag
+    sched_len = c.take<int32_t>(kSchedLenInts);   // list lengths per XCD, the split flag, lengths without small groups
     sched_pairs = c.take<int2>((size_t)kXcd * sched_cap(s));
     chunk_hist = c.take<int32_t>(fast_dispatch(s) ? ((n_ent + 1023) / 1024) * (size_t)s.n_blocks : 0);
+    const size_t small = (size_t)small_rows_of(s);
+    small_ent = c.take<int2>(small ? small * s.n_blocks : 0);
+    small_grp = c.take<int32_t>(small ? (size_t)s.n_blocks : 0);
+    small_cnt = c.take<int32_t>(small ? 2 : 0);
   }
 };
 
@@ -177,6 +194,7 @@ struct DispatchWs {
 struct DenseWs : DispatchWs {
   int32_t *flag = nullptr, *chunk_cnt = nullptr;
   uint16_t *zrow = nullptr, *Ap = nullptr, *DS = nullptr, *part = nullptr;
+  float* ds32 = nullptr;   // activation gradients of the pairs of small groups, [T, top_k]
   void carve_dense(const meft_shape& s, Carver& c) {
     carve(s, c);
     const size_t n_ent = (size_t)s.T * s.top_e;
@@ -189,6 +207,7 @@ struct DenseWs : DispatchWs {
     Ap = zrow ? zrow + bsp : nullptr;
     DS = zrow ? Ap + n_ent * bsp : nullptr;
     part = c.take<uint16_t>(n_ent * s.d);   // per-entry partial rows [T*e, d] bf16
+    ds32 = c.take<float>((size_t)s.T * s.top_k);
   }
 };
 
@@ -503,6 +522,7 @@ void launch_gemm_mfma(const char* name, const P& prob, int grid, hipStream_t st)
 // (token, block) dispatch from sorted per-token block lists: groups, slot maps, XCD tile schedule
 void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dense, bool want_sched, hipStream_t st) {
   const int n_ent = s.T * s.top_e;
+  const int small = dense ? small_rows_of(s) : 0;
   if (fast_dispatch(s)) {
     const int n_chunks = (n_ent + 1023) / 1024;
     const size_t lds = (size_t)16 * s.n_blocks * sizeof(int);
@@ -510,7 +530,7 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
                 s.n_blocks, w.chunk_hist);
     MEFT_LAUNCH("dispatch_scan", dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, w.chunk_hist, n_chunks,
                 s.n_blocks, BM, w.cnt, w.group_off, w.tile_off, sched_cap(s), want_sched ? w.sched_pairs : nullptr,
-                w.sched_len, kTMTok);
+                w.sched_len, kTMTok, small, small ? w.small_ent : nullptr, w.small_grp, w.small_cnt);
     MEFT_LAUNCH("dispatch_place", dispatch_place_kernel, dim3(n_chunks), dim3(1024), lds, st, w.sblk, n_ent,
                 s.n_blocks, s.top_e, w.chunk_hist, w.group_off, w.perm, dense ? w.tok_of_slot : nullptr,
                 w.slot_of_ent, kSlotPad);
@@ -525,7 +545,11 @@ void launch_dispatch(const meft_shape& s, const DispatchWs& w, int BM, bool dens
   }
   if (want_sched) {
     MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks,
-                sched_cap(s), w.sched_pairs, w.sched_len, kTMTok);
+                sched_cap(s), w.sched_pairs, w.sched_len, kTMTok, small);
+  }
+  if (small) {
+    MEFT_LAUNCH("small_lists", small_lists_kernel, dim3(1), dim3(1024), 0, st, w.group_off, s.n_blocks, small,
+                w.small_ent, w.small_grp, w.small_cnt);
   }
 }
 
@@ -536,6 +560,47 @@ void launch_reduce_parts(const meft_shape& s, const uint16_t* part, const Dispat
 #define RP(NV) MEFT_LAUNCH("reduce_parts", (reduce_parts_kernel<NV>), dim3(s.T), dim3(nthr), 0, st, part, w.sblk, w.slot_of_ent, s.d, s.top_e, o)
   switch (nv) { case 1: RP(1); break; case 2: RP(2); break; case 4: RP(4); break; default: RP(8); }
 #undef RP
+}
+
+size_t small_list_bytes(const meft_shape& s) {
+  return (size_t)s.top_k * sizeof(int);   // top_k <= top_e * block_size <= 12288 on the block-dense path
+}
+
+// Launch widths of the kernels that walk the lists of small groups: enough workgroups for the lists of a skewed
+// batch to be taken in one pass, few enough that a launch on a batch without small groups costs next to nothing.
+constexpr int kSmallEntGrid = 1024, kSmallGrpGrid = 128;
+
+// small groups: their rows of `part` as sums of coef * W rows (forward: act and V; backward: ds and K)
+void launch_small_rowsum(const char* name, const meft_shape& s, const DenseWs& w, const void* W, const int32_t* idx,
+                         const float* coef, hipStream_t st) {
+  const int small = small_rows_of(s);
+  if (small == 0) return;
+  const int gx = s.n_blocks * small < kSmallEntGrid ? s.n_blocks * small : kSmallEntGrid;
+  MEFT_LAUNCH(name, small_rowsum_kernel, dim3(gx, (s.d + kSmallCols - 1) / kSmallCols), dim3(256),
+              small_list_bytes(s), st, static_cast<const bf16_t*>(W), idx, coef, w.small_ent, w.small_cnt,
+              w.tok_of_slot, s.d, s.top_k, s.N, s.block_size, reinterpret_cast<bf16_t*>(w.part));
+}
+
+// backward, small groups: the activation gradients of their pairs
+void launch_small_ds(const meft_shape& s, const DenseWs& w, const void* V, const void* dOut, const int32_t* idx,
+                     const float* act, hipStream_t st) {
+  const int small = small_rows_of(s);
+  if (small == 0) return;
+  const int gx = s.n_blocks * small < kSmallEntGrid ? s.n_blocks * small : kSmallEntGrid;
+  MEFT_LAUNCH("small_ds", small_ds_kernel, dim3(gx, kSmallPairSplit), dim3(256), small_list_bytes(s), st,
+              static_cast<const bf16_t*>(V), static_cast<const bf16_t*>(dOut), idx, act, w.small_ent, w.small_cnt,
+              w.tok_of_slot, s.d, s.top_k, s.N, s.block_size, w.ds32);
+}
+
+// backward, small groups: the dV and dK rows of their blocks
+void launch_small_dvdk(const meft_shape& s, const DenseWs& w, const void* h, const void* dOut, const int32_t* idx,
+                       const float* act, void* dK, void* dV, hipStream_t st) {
+  if (small_rows_of(s) == 0) return;
+  const int gx = s.n_blocks < kSmallGrpGrid ? s.n_blocks : kSmallGrpGrid;
+  MEFT_LAUNCH("small_dvdk", small_dvdk_kernel, dim3((s.block_size + kSmallRowChunk - 1) / kSmallRowChunk, gx),
+              dim3(256), 0, st, static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(dOut), idx, act, w.ds32,
+              w.small_grp, w.small_cnt, w.group_off, w.tok_of_slot, s.d, s.top_k, s.N, s.block_size,
+              static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
 }
 
 }  // namespace
@@ -631,9 +696,10 @@ static meft_status fwd_impl(const meft_shape& s, const void* h, const void* K, c
   if (dense) {
     ProbTokNC pv{};
     pv.A = w.Ap; pv.W = vv; pv.group_off = w.group_off; pv.sched = sched; pv.bs = s.block_size; pv.bsp = bsp;
-    pv.d = s.d; pv.part = w.part;
+    pv.d = s.d; pv.part = w.part; pv.big_only = small_rows_of(s) > 0;
     set_gemm_extents(pv, (uint64_t)n_ent * bsp * 2, (uint64_t)s.N * s.d * 2);
     launch_gemm_mfma("value_gemm", pv, tile_bound(s, (s.d + kTN - 1) / kTN), st);
+    launch_small_rowsum("small_value", s, w, V, idx, act, st);
     launch_reduce_parts(s, w.part, w, out, st);
   } else if (s.dtype == MEFT_BF16) {
     launch_gather_fwd<bf16_t>(s, V, idx, act, out, st);
@@ -690,6 +756,8 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbNeuTN pn{};
     pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
     pn.sched = sched; pn.bs = s.block_size; pn.bsp = bsp; pn.d = s.d;
+    const int big_only = small_rows_of(s) > 0;   // the small groups: launch_small_* below
+    pn.big_only = big_only;
     const int n_ent = s.T * s.top_e;
     // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
     // gathers the same dOut rows as the activation-gradient GEMM that follows it
@@ -700,19 +768,23 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     ProbTokKC<kTokMasked> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
     pg.e = s.top_e; pg.bs = s.block_size; pg.bsp = bsp; pg.d = s.d; pg.Ap = w.Ap; pg.DS = w.DS;
+    pg.big_only = big_only;
     set_gemm_extents(pg, (uint64_t)s.T * s.d * 2, (uint64_t)s.N * s.d * 2);
     launch_gemm_mfma("dact_gemm", pg, tile_bound(s, (s.block_size + kTN - 1) / kTN), st);
     if (wait_k && hipStreamWaitEvent(st, wait_k, 0) != hipSuccess) return MEFT_ERR_DEVICE;
+    launch_small_ds(s, w, V, dOut, idx, act, st);
     if (dh) {
       ProbTokNC ph{};
       ph.A = w.DS; ph.W = kk; ph.group_off = w.group_off; ph.sched = sched; ph.bs = s.block_size; ph.bsp = bsp;
-      ph.d = s.d; ph.part = w.part;
+      ph.d = s.d; ph.part = w.part; ph.big_only = big_only;
       set_gemm_extents(ph, (uint64_t)n_ent * bsp * 2, (uint64_t)s.N * s.d * 2);
       launch_gemm_mfma("dh_gemm", ph, tile_bound(s, (s.d + kTN - 1) / kTN), st);
+      launch_small_rowsum("small_dh", s, w, K, idx, w.ds32, st);
       launch_reduce_parts(s, w.part, w, dh, st);
     }
     pn.A = w.DS; pn.zrow = -(n_ent + 1); pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
     launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
+    launch_small_dvdk(s, w, h, dOut, idx, act, dK, dV, st);
     return launch_status();
   }
 
@@ -746,7 +818,7 @@ static void union_front(const meft_shape& s, const UnionGeom& g, const UnionWs& 
   MEFT_LAUNCH("union_maps", union_maps_kernel, dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st, n_S, g.cap,
               s.T, g.vbs, g.nvb, w.sblk, w.perm, w.tok_of_slot, w.slot_of_ent, w.group_off, w.rowflag);
   MEFT_LAUNCH("build_sched", build_sched_kernel, dim3(1), dim3(1024), 0, st, w.group_off, g.nvb, sched_cap(g.vs),
-              w.sched_pairs, w.sched_len, kTMTok);
+              w.sched_pairs, w.sched_len, kTMTok, 0);
   // the row of zeros that pads the contraction over tokens in the weight-gradient GEMMs (vbs % 64 == 0)
   MEFT_LAUNCH("fill_i32", fill_i32_kernel, dim3((g.vbs / 2 + 255) / 256), dim3(256), 0, st,
               reinterpret_cast<int32_t*>(w.zrow), (size_t)g.vbs / 2, 0);
