@@ -575,80 +575,99 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     const int nk = tc.nk;
     bool more = false;
     TileCoord tn;
-    // one k tile out of the current slots; kFirst: the first k16 step starts from zero instead of from acc (the
-    // matrix instruction takes the constant as its addend, so the accumulators are never cleared by hand)
-    auto k_tile = [&](auto first_tag) {
-      constexpr bool kFirst = decltype(first_tag)::value;
+    // The fragments of one k16 step.  Two sets alternate: the LDS reads of step s + 1 are issued before the matrix
+    // instructions of step s, so that their latency passes under those 8 (12) instructions instead of in front of
+    // the next ones.  (Left to itself the compiler reads each step's fragments into the same registers right before
+    // their use, and the matrix pipe idles for an LDS round trip four times per k tile.)
+    struct Frags { bf16x8 a[MI], b[4]; };
+    Frags f0, f1;
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    // transposing read of this lane's 8 values of one operand fragment: low and high k half, 8 bytes each
+    auto tr_pair = [&](const uint16_t* slot, uint32_t lo_off, uint32_t hi_off) -> bf16x8 {
+      const auto* base = (const __attribute__((address_space(3))) char*)(slot);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(base + lo_off));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(base + hi_off));
+      return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // issue the LDS reads of k16 step KS of the current slots
+    auto load_frags = [&](auto ks_tag, Frags& f) {
+      constexpr int ks = decltype(ks_tag)::value;
       const uint16_t* sta = smem + slot_a * kASlotElems;
       const uint16_t* stb = smem + kBRing + slot_b * kBSlotElems;
+      const int c = ks * 2 + fc;   // k-contiguous operands: this lane's 16-byte chunk of the k16 step
+      // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 bytes); that changes neither (k & 7)
+      // nor (k & 3), so the swizzles hold
+      if constexpr (!P::kAMC) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 fa[MI], fb[4];
-        const int c = ks * 2 + fc;   // k-contiguous operands: this lane's 16-byte chunk of the k16 step
-        if constexpr (!P::kAMC) {
+        for (int i = 0; i < MI; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(&sta[offA[i] + ((c ^ keyA[i]) << 3)]);
+      } else {
+        static_assert(!P::kAMC || P::kBNC, "an m-contiguous A comes with an n-contiguous B");
 #pragma unroll
-          for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sta[offA[i] + ((c ^ keyA[i]) << 3)]);
-        }
-        if constexpr (!P::kBNC) {
-          static_assert(!P::kAMC || P::kBNC, "an m-contiguous A comes with an n-contiguous B");
-#pragma unroll
-          for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&stb[offB[j] + ((c ^ keyB[j]) << 3)]);
-        } else {
-          // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 bytes); that changes neither
-          // (k & 7) nor (k & 3), so the swizzles hold
-          const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(stb);
-          uint32_t alo[4], ahi[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
-          u32x2 o[8];
-          if constexpr (P::kAMC) {
-            const uint32_t abase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(sta);
-            const uint32_t xa[4] = {abase + tra_lo[0], abase + tra_hi[0], abase + tra_lo[1], abase + tra_hi[1]};
-            u32x2 oa[4];
-            if (ks == 0) tr_read12<0, 0>(oa, o, xa, alo, ahi);
-            else if (ks == 1) tr_read12<4096, 8192>(oa, o, xa, alo, ahi);
-            else if (ks == 2) tr_read12<8192, 16384>(oa, o, xa, alo, ahi);
-            else tr_read12<12288, 24576>(oa, o, xa, alo, ahi);
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-              const u32x4 w = {oa[2 * i].x, oa[2 * i].y, oa[2 * i + 1].x, oa[2 * i + 1].y};
-              fa[i] = __builtin_bit_cast(bf16x8, w);
-            }
-          } else {
-            if (ks == 0) tr_read8<0>(o, alo, ahi);
-            else if (ks == 1) tr_read8<8192>(o, alo, ahi);
-            else if (ks == 2) tr_read8<16384>(o, alo, ahi);
-            else tr_read8<24576>(o, alo, ahi);
-          }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
-            fb[j] = __builtin_bit_cast(bf16x8, w);
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (kFirst && ks == 0) {
-              const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], zero, 0, 0, 0);
-            } else {
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-            }
-          }
+        for (int i = 0; i < 2; ++i) f.a[i] = tr_pair(sta, tra_lo[i] + ks * 4096u, tra_hi[i] + ks * 4096u);
       }
+      if constexpr (!P::kBNC) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(&stb[offB[j] + ((c ^ keyB[j]) << 3)]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f.b[j] = tr_pair(stb, tr_lo[j] + ks * 8192u, tr_hi[j] + ks * 8192u);
+      }
+    };
+    // kZero: the step starts from zero instead of from acc (the matrix instruction takes the constant as its addend,
+    // so the accumulators are never cleared by hand)
+    auto mma = [&](auto zero_tag, const Frags& f) {
+      constexpr bool kZero = decltype(zero_tag)::value;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if constexpr (kZero) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], zero, 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+          }
+        }
+    };
+    // nothing moves across: the order of reads and matrix instructions below is the schedule
+#define MEFT_FENCE() __builtin_amdgcn_sched_barrier(0)
+    // Steps 0..2 of a k tile whose first fragments (f0) are on their way; its step 3 (f1) is left to the caller.
+    auto k_steps = [&](auto first_tag) {
+      load_frags(std::integral_constant<int, 1>{}, f1);
+      MEFT_FENCE();
+      mma(first_tag, f0);
+      MEFT_FENCE();
+      load_frags(std::integral_constant<int, 2>{}, f0);
+      MEFT_FENCE();
+      mma(std::false_type{}, f1);
+      MEFT_FENCE();
+      load_frags(std::integral_constant<int, 3>{}, f1);
+      MEFT_FENCE();
+      mma(std::false_type{}, f0);
+      MEFT_FENCE();
       slot_a = slot_a + 1 == SA ? 0 : slot_a + 1;
       slot_b = slot_b + 1 == SB ? 0 : slot_b + 1;
     };
     MEFT_BARRIER_LDS();   // the loaders have seen the tile's first k tile land
     wg += step;
     more = next_tile(wg, tn);
-    k_tile(std::true_type{});
+    load_frags(std::integral_constant<int, 0>{}, f0);
+    MEFT_FENCE();
+    k_steps(std::true_type{});
     for (int kt = 1; kt < nk; ++kt) {
+      // The barrier for k tile kt sits in front of the last matrix instructions of k tile kt - 1: every LDS read of
+      // that position has returned (the barrier macro waits for them), so the loaders may have its slots, and the
+      // first reads of the new position pass under those instructions.
       MEFT_BARRIER_LDS();
-      k_tile(std::false_type{});
+      load_frags(std::integral_constant<int, 0>{}, f0);
+      MEFT_FENCE();
+      mma(std::false_type{}, f1);
+      MEFT_FENCE();
+      k_steps(std::false_type{});
     }
+    mma(std::false_type{}, f1);
+#undef MEFT_FENCE
 
     // ---- epilogue, out of the registers.  acc[i][j][r] is C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4
     // and n = wn + j*32 + lane%32.  For a register pair (r, r+1), r even, an even lane (column c) keeps its value of
