@@ -31,7 +31,7 @@ constexpr int kSlotPad = 192;
 // the contraction is split `ksplit` ways over workgroups to fill the chip; split s writes its partial
 // scores to p + s*T*n_blocks and the top-e kernel adds the partials in a fixed order.
 struct ProbRouter {
-  static constexpr int kTM = kTMNeu, kSA = 3, kSB = 3;   // 128-row tiles: twice as many workgroups for a small problem
+  static constexpr int kTM = kTMNeu, kSA = 3, kSB = 3, kCW = 4;   // 128-row tiles: twice as many workgroups for a small problem
   static constexpr int kLoaders = 2;
   static constexpr bool kAMC = false;
   static constexpr bool kBNC = false;
@@ -77,7 +77,7 @@ constexpr int kTokScores = 0, kTokMasked = 1, kTokRelu = 2;
 
 template <int MODE>
 struct ProbTokKC {
-  static constexpr int kTM = kTMTok, kSA = MEFT_TOK_SA, kSB = MEFT_TOK_SB;
+  static constexpr int kTM = kTMTok, kSA = MEFT_TOK_SA, kSB = MEFT_TOK_SB, kCW = 4;
   static constexpr int kLoaders = 2;
   static constexpr bool kAMC = false;
   static constexpr bool kBNC = false;
@@ -154,7 +154,7 @@ struct ProbTokKC {
 // Token-major, B contiguous along n: part[slot, :] = A[slot, 0:bs] . W_b   (W = V: forward value sum;
 // W = K: dh).  A is slot-major [slots, bsp] with zero padding in columns bs..bsp.
 struct ProbTokNC {
-  static constexpr int kTM = kTMTok, kSA = MEFT_TOK_SA, kSB = MEFT_TOK_SB;
+  static constexpr int kTM = kTMTok, kSA = MEFT_TOK_SA, kSB = MEFT_TOK_SB, kCW = 4;
   static constexpr int kLoaders = 4;   // measured: 0.375 -> 0.339 ms (value sum) against two
   static constexpr bool kAMC = false;
   static constexpr bool kBNC = true;
@@ -200,8 +200,10 @@ struct ProbTokNC {
 // come from a row of zeros that the workspace keeps in front of the activation matrices, those of X are any valid
 // rows.  Only rows whose neuron is touched are written.
 struct ProbNeuTN {
-  static constexpr int kTM = kTMNeu, kSA = 3, kSB = 3;
-  static constexpr int kLoaders = 4;   // measured: 0.425 -> 0.388 ms (dV) against two
+  // 256 x 256 tiles, eight compute waves that request their operands themselves, two slots per ring; or 128 x 256
+  // with four compute and four loader waves (measured: 0.425 -> 0.388 ms (dV) against two)
+  static constexpr int kTM = kTMNeuW, kSA = kTMNeuW == 256 ? 2 : 3, kSB = kSA, kCW = kTMNeuW == 256 ? 8 : 4;
+  static constexpr int kLoaders = kTMNeuW == 256 ? 0 : 4;
   static constexpr bool kAMC = true;
   static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = true;

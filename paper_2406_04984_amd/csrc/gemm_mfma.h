@@ -9,34 +9,43 @@
 //     dOut, h are contiguous in d: the value sum of Eq. 4, dh, dK, dV;
 //   A m-contiguous (rows indexed by k): dK, dV, whose A operand is the slot-major activation matrix, read as it is.
 //
-// Tile TM (m) x 256 (n) x 64 (k) with TM = 192 for the token-major problems and 128 for the router and the
-// neuron-major problems (a policy's kTM); 4 compute waves as 2 x 2, each wave TM/2 x 128 = (TM/64) x 4 MFMA tiles,
-// plus two or four loader waves that own the whole global -> LDS traffic (16 B per lane).  The operands have a ring
-// each in LDS: kSA slots of TM x 64 for A, kSB slots of 256 x 64 for B (three and three with TM = 128, two and three
-// with TM = 192: 144 KB both ways).  The 192-row tile moves 22 % fewer operand bytes per flop than the 128-row one,
-// and operand delivery from L2 is what bounds these kernels; its accumulators (192 registers per lane) still leave
-// room for the loader waves on the same SIMDs, which a 256 x 256 tile's would not.  LDS layouts are XOR-swizzled so
-// that both the linear DMA writes and the fragment reads are free of bank conflicts:
+// Tile TM (m) x 256 (n) x 64 (k), a policy's kTM.  Two shapes of workgroup:
+//   kTM = 128 (or 192): 4 compute waves as 2 x 2, each wave TM/2 x 128 = (TM/64) x 4 MFMA tiles, plus two or four
+//     loader waves that own the whole global -> LDS traffic (16 B per lane).  Ring depths kSA, kSB up to three.
+//     Used by the router, the token-major problems and (as an option) the neuron-major ones.
+//   kTM = 256: 8 compute waves as 4 x 2, each wave 64 x 128, and no loader waves (kLoaders = 0): the accumulators of
+//     8 waves leave no registers for further waves on their SIMDs, so every compute wave requests an eighth of the
+//     operands itself, right after each barrier.  Two slots per ring (128 KB).  Used by the neuron-major problems
+//     (dV, dK), whose output has no ragged edge: a third fewer operand bytes per flop through L2 -> LDS, and half as
+//     many store phases.  Measured at the LLaMA-7B-shaped configuration: dV 0.355 -> 0.340 ms, dK 0.345 -> 0.339 ms.
+// The operands have a ring each in LDS: kSA slots of TM x 64 for A, kSB slots of 256 x 64 for B.  (A 192-row tile
+// for the token-major problems moves 22 % fewer operand bytes per flop than the 128-row one and was measured 15 %
+// faster per flop, but their groups then fill a whole number of tiles worse and the step as a whole did not gain.)
+// LDS layouts are XOR-swizzled so that both the linear DMA writes and the fragment reads are free of bank conflicts:
 //   k-contiguous operand: rows of 64 k = 8 chunks of 16 B; logical chunk c of row r sits at chunk
 //     c ^ ((r >> 1) & 7); fragments are read with ds_read_b128.
-//   n-contiguous B: rows of 256 n = 32 chunks; logical chunk c of row k sits at chunk c ^ (2 * (k & 7));
-//   m-contiguous A: rows of 128 m = 16 chunks; logical chunk c of row k sits at chunk c ^ (4 * (k & 3));
-//     both are read with the transposing ds_read_b64_tr_b16, which hands lane i of a 16-lane group the four
+//   n-contiguous B, and m-contiguous A of 256 rows: rows of 256 = 32 chunks; logical chunk c of row k sits at chunk
+//     c ^ (2 * (k & 7));
+//   m-contiguous A of 128 rows: 16 chunks per row; logical chunk c of row k sits at chunk c ^ (4 * (k & 3));
+//     these are read with the transposing ds_read_b64_tr_b16, which hands lane i of a 16-lane group the four
 //     k-consecutive values of column i of a 4 x 16 block.
 //
 // The k tiles of all the tiles a workgroup works through form ONE stream through the rings: right after the barrier
-// that hands position s to the compute waves the loaders request A of position s + kSA - 1 and B of position
-// s + kSB - 1 (the operand with the shorter lead first), whether or not those belong to the next output tile, so the
-// operand pipeline never drains at a tile boundary.  There is exactly one
-// workgroup barrier per k tile of the stream, executed by all the waves.  (An extra barrier at the end of every
-// tile, releasing its last stage before the stores so that the loaders request a third k tile during the epilogue,
-// was measured and did not pay.)
+// that hands position s to the compute waves, A of position s + kSA - 1 and B of position s + kSB - 1 are requested
+// (the operand with the shorter lead first), whether or not those belong to the next output tile, so the operand
+// pipeline never drains at a tile boundary.  There is exactly one workgroup barrier per k tile of the stream,
+// executed by all the waves.  (An extra barrier at the end of every tile, releasing its last stage before the stores
+// so that the loaders request a third k tile during the epilogue, was measured and did not pay.)
+//
+// With loader waves, a compute wave keeps two register sets of fragments: the LDS reads of k16 step s + 1 are issued
+// before the matrix instructions of step s, and the barrier of the next k tile sits in front of the last matrix
+// instructions of the current one.
 //
 // The epilogue needs neither LDS nor barriers: neighbouring lanes exchange one accumulator value through a DPP
 // move, so that every lane holds two adjacent columns of one row, and hands them to the policy, which stores them
 // (4 bytes of bf16, converted before the exchange, or 8 bytes of fp32 per lane; a half wave writes 64 or 128
-// contiguous bytes of each of two rows per instruction).  While the compute waves store, the loaders are already two k tiles into the next
-// tile.
+// contiguous bytes of each of two rows per instruction).  While the compute waves store, the loaders are already
+// up to two k tiles into the next tile.
 //
 // Workgroups are mapped to tiles XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs,
 // so workgroup id w works for XCD w % 8, and all tiles of one group (block of neurons) are given to
@@ -55,22 +64,29 @@ constexpr int kTN = 256, kTK = 64;
 #define MEFT_TOK_SA 3
 #define MEFT_TOK_SB 3
 #endif
+#ifndef MEFT_NEU_TM
+#define MEFT_NEU_TM 256
+#endif
 constexpr int kTMTok = MEFT_TOK_TM;    // tile rows of the token-major problems (groups of tokens against a block's rows)
-constexpr int kTMNeu = 128;    // tile rows of the router and of the neuron-major problems
+constexpr int kTMNeu = 128;            // tile rows of the router
+constexpr int kTMNeuW = MEFT_NEU_TM;   // tile rows of the neuron-major problems (dV, dK): 256, or 128
 constexpr int kBSlotElems = kTN * kTK;                         // one B slot: 32 KB
 constexpr int kIdRingSlots = 4;                                // k tiles of gathered-row numbers kept per loader
-constexpr int kMaxLoaders = 4;
 constexpr int kXcd = 8;
-// LDS of a launch: the two operand rings and, where the numbers of gathered B rows travel through LDS, 1 KB per loader
+// waves that request operands: the policy's loader waves, or (kLoaders == 0) its compute waves themselves
+template <class P>
+constexpr int loading_waves() { return P::kLoaders ? P::kLoaders : P::kCW; }
+// LDS of a launch: the two operand rings and, where the numbers of gathered B rows travel through LDS, 1 KB per
+// loading wave
 template <class P>
 constexpr int operand_lds_bytes() { return (P::kSA * P::kTM + P::kSB * kTN) * kTK * 2; }
 template <class P>
 constexpr int gemm_lds_bytes() {
-  return operand_lds_bytes<P>() + (P::kRowIdsInMemory ? kMaxLoaders * kIdRingSlots * 64 * 4 : 0);
+  return operand_lds_bytes<P>() + (P::kRowIdsInMemory ? loading_waves<P>() * kIdRingSlots * 64 * 4 : 0);
 }
-// threads of a launch: four compute waves plus the policy's loader waves
+// threads of a launch: the policy's compute waves plus its loader waves
 template <class P>
-constexpr int gemm_threads() { return 256 + 64 * P::kLoaders; }
+constexpr int gemm_threads() { return 64 * (P::kCW + P::kLoaders); }
 
 #define MEFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define MEFT_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -137,31 +153,12 @@ struct TileCoord {
 //                the policy wants next to the two values of (m, n), e.g. a mask; called for every position of the
 //                tile, stored or not, so the policy clamps m and n to valid ones
 
-// Eight transposing LDS reads (the four n-contiguous B fragments of one k16 step, low and high k half)
-// followed by the wait for them.  Written as one asm block: issued through the builtin, the compiler
-// would order these reads after every outstanding global->LDS load (it cannot tell the stages apart),
-// which would drain the operand pipeline at every k tile.  The barrier that hands a stage over already
-// guarantees that the stage read here has landed.
-template <int OFF>
-__device__ __forceinline__ void tr_read8(u32x2 (&o)[8], const uint32_t (&alo)[4], const uint32_t (&ahi)[4]) {
-  asm volatile(
-      "ds_read_b64_tr_b16 %0, %8 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %1, %9 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %2, %10 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %3, %11 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %4, %12 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %6, %14 offset:%16\n\t"
-      "ds_read_b64_tr_b16 %7, %15 offset:%16\n\t"
-      "s_waitcnt lgkmcnt(0)"
-      : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]), "=&v"(o[6]), "=&v"(o[7])
-      : "v"(alo[0]), "v"(ahi[0]), "v"(alo[1]), "v"(ahi[1]), "v"(alo[2]), "v"(ahi[2]), "v"(alo[3]), "v"(ahi[3]),
-        "n"(OFF)
-      : "memory");
-}
-
 // Twelve transposing LDS reads of one k16 step (the two m-contiguous A fragments and the four n-contiguous B
 // fragments, low and high k half each) followed by the wait for them.  xa = {A0 low, A0 high, A1 low, A1 high}.
+// Written as one asm block for the compute waves that also request operands: issued through the builtin, the
+// compiler would order these reads after every outstanding global->LDS load (it cannot tell the slots apart),
+// which would drain the operand pipeline at every k tile.  The barrier that hands a position over already
+// guarantees that the slots read here have landed.
 template <int OFFA, int OFFB>
 __device__ __forceinline__ void tr_read12(u32x2 (&oa)[4], u32x2 (&ob)[8], const uint32_t (&xa)[4],
                                           const uint32_t (&blo)[4], const uint32_t (&bhi)[4]) {
@@ -190,11 +187,11 @@ __device__ __forceinline__ void tr_read12(u32x2 (&oa)[4], u32x2 (&ob)[8], const 
 // operand loads that have to have landed instead.)
 #define MEFT_BARRIER_LDS() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
-// Four compute waves (tid 0..255) and P::kLoaders loader waves (two, or four where the loaders' own instruction
-// stream paces the loads: row numbers to look up, an address to form per load).  The loaders own the whole global -> LDS traffic:
-// measured on gfx950 the operand path, not the matrix cores or LDS, bounds these contractions (a compute unit keeps
-// about a hundred 128-byte read requests in flight, no more), and a wave that both requests operands and issues
-// MFMAs keeps neither queue full.  The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ...
+// P::kCW compute waves (the first waves of the workgroup) and P::kLoaders loader waves (two, or four where the
+// loaders' own instruction stream paces the loads: row numbers to look up, an address to form per load; none where
+// the compute waves load).  Measured on gfx950 the operand path, not the matrix cores or LDS latency, bounds these
+// contractions (a compute unit keeps about a hundred 128-byte read requests in flight on average), and with four
+// compute waves a wave that both requests operands and issues MFMAs keeps neither queue full.  The workgroup is persistent: it works through tiles wg, wg + gridDim.x, ...
 // (gridDim.x is a multiple of 8, so it stays on one XCD's list).
 // kBuf: the operand loads are buffer loads (both operand matrices smaller than 4 GB) instead of global loads
 __device__ __forceinline__ uint32_t byte_off(const uint16_t* ptr, const uint16_t* base) {
@@ -203,16 +200,20 @@ __device__ __forceinline__ uint32_t byte_off(const uint16_t* ptr, const uint16_t
 
 template <class P, bool kBuf>
 __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, int n_tiles_bound) {
-  constexpr int kLoaders = P::kLoaders;
+  constexpr int kCW = P::kCW;                       // compute waves: 4 (2 x 2) or 8 (4 x 2)
+  constexpr bool kSelf = P::kLoaders == 0;          // the compute waves request the operands themselves
+  constexpr int kLoaders = loading_waves<P>();      // waves that request operands
   constexpr int TM = P::kTM, SA = P::kSA, SB = P::kSB;
-  constexpr int MI = TM / 64;                       // 32-row MFMA tiles per compute wave: 2 or 3
+  constexpr int WM = TM / (kCW / 2);                // rows of a compute wave: 64 or 96
+  constexpr int MI = WM / 32;                       // 32-row MFMA tiles per compute wave: 2 or 3
   constexpr int kASlotElems = TM * kTK;
   constexpr int kBRing = SA * kASlotElems;          // element offset of the B ring
-  static_assert(kLoaders == 2 || kLoaders == 4, "loader waves: 2 or 4");
-  static_assert(TM == 128 || TM == 192, "tile rows: 128 or 192");
+  static_assert(kLoaders == 2 || kLoaders == 4 || kLoaders == 8, "waves that load: 2, 4 or 8");
+  static_assert((kCW == 4 && (TM == 128 || TM == 192)) || (kCW == 8 && TM == 256), "tile rows: 128, 192 or 256");
   static_assert(SA >= 2 && SA <= 3 && SB >= 2 && SB <= 3, "ring depths: 2 or 3");
-  static_assert(!P::kAMC || TM == 128, "the m-contiguous A layout is written for 128 rows");
-  static_assert(!P::kRowIdsInMemory || (SA == 3 && SB == 3), "row numbers through LDS: three slots each");
+  static_assert(!P::kAMC || TM == 128 || TM == 256, "the m-contiguous A layouts are written for 128 and 256 rows");
+  static_assert(!kSelf || (P::kAMC && P::kBNC && SA == 2 && SB == 2 && kCW == 8),
+                "compute waves that load: written for the neuron-major problems with two slots per ring");
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -223,9 +224,10 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
   TileCoord tc;
   if (!next_tile(blockIdx.x, tc)) return;   // the same answer in every wave
 
-  if (wave >= 4) {
-    // ------------------------------------------------------------------ loader waves
-    const int lw = wave - 4;
+  // ---------------------------------------------------------------------- operand requests
+  // (state and steps of a wave that loads: a loader wave, or with kSelf every compute wave; dead code in the compute
+  // waves of a launch with loader waves)
+    const int lw = kSelf ? wave : wave - kCW;
     constexpr int LA = TM / 8 / kLoaders;    // A wave-loads (1 KB each) per loader and slot: 12, 8, 6 or 4
     constexpr int LB = kTN / 8 / kLoaders;   // B wave-loads (1 KB each) per loader and slot: 16 or 8
     constexpr int DA = SA - 1, DB = SB - 1;  // positions ahead of the barrier at which A and B are requested
@@ -247,9 +249,10 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     int wg_c = blockIdx.x, nk_c = tc.nk;
 
     // A, k-contiguous: a wave-load covers 8 rows (m) x 128 bytes; fixed row pointers per tile, advanced by k.
-    // A, m-contiguous: a wave-load covers 4 rows (k) x 256 bytes; lane l fetches the 16-byte chunk
+    // A, m-contiguous, 128 rows: a wave-load covers 4 rows (k) x 256 bytes; lane l fetches the 16-byte chunk
     //   (l & 15) ^ (4 * (row & 3)) of its row (the LDS swizzle; row & 3 == (l >> 4) & 3 for every load), so one
-    //   column offset per tile serves all the loads.
+    //   column offset per tile serves all the loads.  With 256 rows the slot has the shape of an n-contiguous B slot
+    //   and is filled the same way.
     // B, k-contiguous: like A, 8 rows (n) x 128 bytes.
     // B, n-contiguous: a wave-load covers two k rows (lanes 0..31 the even one, lanes 32..63 the odd one), 512 bytes
     //   of each; lane l fetches the chunk (l & 31) ^ (2 * (row & 7)); row & 7 only depends on i & 3, so four
@@ -269,7 +272,14 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     auto setup_a = [&]() {
       const TileCoord& t = ca.t;
       if constexpr (kBuf) {
-        if constexpr (P::kAMC) {
+        if constexpr (P::kAMC && TM == 256) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
+            const int col = t.m0 + chunk * 8, last = p.a_cols(t) - 8;
+            oa[q] = byte_off(p.a_mat() + (col > last ? last : col), p.a_base());
+          }
+        } else if constexpr (P::kAMC) {
           const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
           const int col = t.m0 + chunk * 8, last = p.a_cols(t) - 8;
           const uint32_t o = byte_off(p.a_mat() + (col > last ? last : col), p.a_base());
@@ -283,7 +293,14 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
           }
         }
       } else {
-        if constexpr (P::kAMC) {
+        if constexpr (P::kAMC && TM == 256) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int chunk = (lane & 31) ^ (2 * ((2 * q + half) & 7));
+            const int col = t.m0 + chunk * 8, last = p.a_cols(t) - 8;
+            pa[q] = p.a_mat() + ((col > last ? last : col) - q * 512);   // clamp (rows beyond Mrows are never stored)
+          }
+        } else if constexpr (P::kAMC) {
           const int chunk = (lane & 15) ^ (4 * ((lane >> 4) & 3));
           const int col = t.m0 + chunk * 8, last = p.a_cols(t) - 8;
           const int acol = col > last ? last : col;                       // clamp (rows beyond Mrows are never stored)
@@ -380,7 +397,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
           if constexpr (P::kAMC) {
-            const int row = p.a_krow(t, ca.k * kTK + 4 * (lw * LA + i) + (lane >> 4));
+            const int row = p.a_krow(t, ca.k * kTK + (TM == 256 ? 2 * (lw * LA + i) + half : 4 * (lw * LA + i) + (lane >> 4)));
             MEFT_LOAD_1K_BUF(rsrc_a, oa[i & 3] + (uint32_t)row * (uint32_t)a_row_bytes, 0, my_a, i);
           } else {
             MEFT_LOAD_1K_BUF(rsrc_a, oa[i], k_bytes, my_a, i);
@@ -390,7 +407,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
           if constexpr (P::kAMC) {
-            const int row = p.a_krow(t, ca.k * kTK + 4 * (lw * LA + i) + (lane >> 4));
+            const int row = p.a_krow(t, ca.k * kTK + (TM == 256 ? 2 * (lw * LA + i) + half : 4 * (lw * LA + i) + (lane >> 4)));
             MEFT_LOAD_1K(reinterpret_cast<const char*>(pa[i & 3]) + (int64_t)row * a_row_bytes, my_a, i);
           } else {
             MEFT_LOAD_1K(pa[i] + ca.k * kTK, my_a, i);
@@ -430,8 +447,15 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
               "=&v"(ids[13]), "=&v"(ids[14]), "=&v"(ids[15])
             : "v"(a)
             : "memory");
+        } else if constexpr (LB == 4) {
+        asm volatile(
+            "ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:8\n\tds_read_b32 %2, %4 offset:16\n\t"
+            "ds_read_b32 %3, %4 offset:24\n\ts_waitcnt lgkmcnt(0)"
+            : "=&v"(ids[0]), "=&v"(ids[1]), "=&v"(ids[2]), "=&v"(ids[3])
+            : "v"(a)
+            : "memory");
         } else {
-        static_assert(LB == 16 || LB == 8, "row-number reads are written out for 16 and 8 loads");
+        static_assert(LB == 16 || LB == 8 || LB == 4, "row-number reads are written out for 16, 8 and 4 loads");
         asm volatile(
             "ds_read_b32 %0, %8\n\tds_read_b32 %1, %8 offset:8\n\tds_read_b32 %2, %8 offset:16\n\t"
             "ds_read_b32 %3, %8 offset:24\n\tds_read_b32 %4, %8 offset:32\n\tds_read_b32 %5, %8 offset:40\n\t"
@@ -499,6 +523,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       return a && b;
     };
 
+  if (kSelf || wave >= kCW) {
     setup_a();
     setup_b();
     if constexpr (P::kBNC && P::kRowIdsInMemory) {
@@ -513,8 +538,12 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     for (int s = 1; s < DA; ++s) full = request_a() && full;
 #pragma unroll
     for (int s = 1; s < DB; ++s) full = request_b() && full;
+    // compute waves that load: position 0 has to have landed at the first barrier (later positions are awaited
+    // before the barrier that hands them over)
+    if constexpr (kSelf) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    for (;;) {
+    // ------------------------------------------------------------------ loader waves
+    for (; !kSelf;) {
       for (int kt = 0; kt < nk_c; ++kt) {
         // The position handed over now has landed once at most the kAhead most recent loads are outstanding (the
         // counter retires in issue order), provided the last batch of requests was complete; near the end of the
@@ -532,7 +561,6 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
   }
 
   // -------------------------------------------------------------------- compute waves
-  constexpr int WM = TM / 2;   // rows of a compute wave: 64 or 96
   const int wm = (wave >> 1) * WM, wn = (wave & 1) * 128;
   const int fr = lane & 31, fc = lane >> 5;
   // k-contiguous operands: element offsets of this lane's fragment rows inside a slot, and their swizzle keys
@@ -551,8 +579,9 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int m = wm + i * 32 + 16 * (gq & 1) + 4 * (s & 3);
-      tra_lo[i] = (uint32_t)(k_lo * TM + (((m >> 3) ^ (4 * (k_lo & 3))) << 3) + (m & 7)) * 2u;
-      tra_hi[i] = (uint32_t)(k_hi * TM + (((m >> 3) ^ (4 * (k_hi & 3))) << 3) + (m & 7)) * 2u;
+      const int x_lo = TM == 256 ? 2 * (k_lo & 7) : 4 * (k_lo & 3), x_hi = TM == 256 ? 2 * (k_hi & 7) : 4 * (k_hi & 3);
+      tra_lo[i] = (uint32_t)(k_lo * TM + (((m >> 3) ^ x_lo) << 3) + (m & 7)) * 2u;
+      tra_hi[i] = (uint32_t)(k_hi * TM + (((m >> 3) ^ x_hi) << 3) + (m & 7)) * 2u;
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -581,6 +610,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
     // their use, and the matrix pipe idles for an LDS round trip four times per k tile.)
     struct Frags { bf16x8 a[MI], b[4]; };
     Frags f0, f1;
+    constexpr uint32_t kStepA = 16 * TM * 2;   // bytes of 16 k rows of an m-contiguous A slot
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef short s16x8 __attribute__((ext_vector_type(8)));
     // transposing read of this lane's 8 values of one operand fragment: low and high k half, 8 bytes each
@@ -596,15 +626,15 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       const uint16_t* sta = smem + slot_a * kASlotElems;
       const uint16_t* stb = smem + kBRing + slot_b * kBSlotElems;
       const int c = ks * 2 + fc;   // k-contiguous operands: this lane's 16-byte chunk of the k16 step
-      // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 bytes); that changes neither (k & 7)
-      // nor (k & 3), so the swizzles hold
+      // k16 step ks starts 16 rows further (B: 8192 bytes, m-contiguous A: 4096 or 8192 bytes); that changes neither
+      // (k & 7) nor (k & 3), so the swizzles hold
       if constexpr (!P::kAMC) {
 #pragma unroll
         for (int i = 0; i < MI; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(&sta[offA[i] + ((c ^ keyA[i]) << 3)]);
       } else {
         static_assert(!P::kAMC || P::kBNC, "an m-contiguous A comes with an n-contiguous B");
 #pragma unroll
-        for (int i = 0; i < 2; ++i) f.a[i] = tr_pair(sta, tra_lo[i] + ks * 4096u, tra_hi[i] + ks * 4096u);
+        for (int i = 0; i < 2; ++i) f.a[i] = tr_pair(sta, tra_lo[i] + ks * kStepA, tra_hi[i] + ks * kStepA);
       }
       if constexpr (!P::kBNC) {
 #pragma unroll
@@ -649,6 +679,58 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       slot_a = slot_a + 1 == SA ? 0 : slot_a + 1;
       slot_b = slot_b + 1 == SB ? 0 : slot_b + 1;
     };
+    if constexpr (kSelf) {
+      // Compute waves that load.  The compiler orders every LDS read it knows of behind all outstanding global -> LDS
+      // loads (it cannot tell the slots apart), which would undo the prefetch, so here the fragments are read by asm
+      // blocks that wait for themselves; with two compute waves per SIMD the other wave's matrix instructions cover
+      // that wait.  A position's operands are requested right after the barrier that hands over the position before
+      // it, and awaited (vmcnt) right before the barrier that hands it over; the first position of a tile is awaited
+      // before the previous tile's stores, so that no barrier waits for stores.
+      auto k_tile_self = [&](auto first_tag) {
+        const uint16_t* sta = smem + slot_a * kASlotElems;
+        const uint16_t* stb = smem + kBRing + slot_b * kBSlotElems;
+        const uint32_t abase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(sta);
+        const uint32_t sbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(stb);
+        const uint32_t xa[4] = {abase + tra_lo[0], abase + tra_hi[0], abase + tra_lo[1], abase + tra_hi[1]};
+        uint32_t alo[4], ahi[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { alo[j] = sbase + tr_lo[j]; ahi[j] = sbase + tr_hi[j]; }
+        auto step16 = [&](auto ks_tag, auto zero_tag) {
+          constexpr int ks = decltype(ks_tag)::value;
+          u32x2 oa[4], o[8];
+          tr_read12<ks * (int)kStepA, ks * 8192>(oa, o, xa, alo, ahi);
+          Frags f;
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            const u32x4 w = {oa[2 * i].x, oa[2 * i].y, oa[2 * i + 1].x, oa[2 * i + 1].y};
+            f.a[i] = __builtin_bit_cast(bf16x8, w);
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const u32x4 w = {o[2 * j].x, o[2 * j].y, o[2 * j + 1].x, o[2 * j + 1].y};
+            f.b[j] = __builtin_bit_cast(bf16x8, w);
+          }
+          mma(zero_tag, f);
+        };
+        step16(std::integral_constant<int, 0>{}, first_tag);
+        step16(std::integral_constant<int, 1>{}, std::false_type{});
+        step16(std::integral_constant<int, 2>{}, std::false_type{});
+        step16(std::integral_constant<int, 3>{}, std::false_type{});
+        slot_a = slot_a + 1 == SA ? 0 : slot_a + 1;
+        slot_b = slot_b + 1 == SB ? 0 : slot_b + 1;
+      };
+      MEFT_BARRIER_LDS();   // (the tile's first position was awaited before: see above)
+      request_batch();
+      wg += step;
+      more = next_tile(wg, tn);
+      k_tile_self(std::true_type{});
+      for (int kt = 1; kt < nk; ++kt) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        request_batch();
+        k_tile_self(std::false_type{});
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
     MEFT_BARRIER_LDS();   // the loaders have seen the tile's first k tile land
     wg += step;
     more = next_tile(wg, tn);
@@ -667,6 +749,7 @@ __global__ __launch_bounds__(gemm_threads<P>(), 1) void gemm_mfma_kernel(P p, in
       k_steps(std::false_type{});
     }
     mma(std::false_type{}, f1);
+    }
 #undef MEFT_FENCE
 
     // ---- epilogue, out of the registers.  acc[i][j][r] is C[m][n] with m = wm + i*32 + (r/4)*8 + (lane/32)*4 + r%4

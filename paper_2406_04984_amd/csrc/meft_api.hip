@@ -751,7 +751,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
                 touched, n_touched);
     const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
     // every listed group has the same tiles; in the worst case one XCD holds all groups
-    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + kTMNeu - 1) / kTMNeu) * ((s.d + kTN - 1) / kTN);
+    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + ProbNeuTN::kTM - 1) / ProbNeuTN::kTM) * ((s.d + kTN - 1) / kTN);
     const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
     ProbNeuTN pn{};
     pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
@@ -916,7 +916,7 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
     launch_gemm_mfma("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(g.vs, w.part, w, dh, st);
   }
-  const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + kTMNeu - 1) / kTMNeu) * ((s.d + kTN - 1) / kTN);
+  const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + ProbNeuTN::kTM - 1) / ProbNeuTN::kTM) * ((s.d + kTN - 1) / kTN);
   const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
   ProbNeuTN pn{};
   pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;
