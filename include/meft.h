@@ -46,6 +46,9 @@
  *        row is rounded to bf16 when stored, the partial rows are summed in fp32 (blocks in ascending id) and
  *        the sum is rounded again.  out and dh therefore see three roundings (operand, partial row, result),
  *        dK and dV two (operand, result); each rounding has relative size at most 2^-9.
+ *      A block that the batch routes at most min(16, top_e * block_size / top_k) tokens to is computed pair by pair
+ *      instead (the paper's router is not balanced): for its entries the two operand roundings do not happen
+ *      (act and ds stay fp32); the partial-row and result roundings are the same.
  *    Precision: a bf16 shape runs on the matrix cores when d is a multiple of 64, block_size >= 16,
  *    64 * top_k >= top_e * block_size and top_e * block_size <= 12288; otherwise on the per-pair kernels.
  *  - Host threads: the entry points may be called from several host threads; their host side (validation, launches,
