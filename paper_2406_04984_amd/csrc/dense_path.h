@@ -199,11 +199,13 @@ struct ProbTokNC {
 // so no transposed copy of the activations exists.  The contraction length is padded to 64: the padding rows of A
 // come from a row of zeros that the workspace keeps in front of the activation matrices, those of X are any valid
 // rows.  Only rows whose neuron is touched are written.
+// TM = 256: 256 x 256 tiles, eight compute waves that request their operands themselves, two slots per ring; TM = 128:
+// 128 x 256 with four compute and four loader waves (measured: 0.425 -> 0.388 ms (dV) against two).  The host takes
+// the larger tile where it does not add rows beyond the block (neu_tile_rows).
+template <int TM>
 struct ProbNeuTN {
-  // 256 x 256 tiles, eight compute waves that request their operands themselves, two slots per ring; or 128 x 256
-  // with four compute and four loader waves (measured: 0.425 -> 0.388 ms (dV) against two)
-  static constexpr int kTM = kTMNeuW, kSA = kTMNeuW == 256 ? 2 : 3, kSB = kSA, kCW = kTMNeuW == 256 ? 8 : 4;
-  static constexpr int kLoaders = kTMNeuW == 256 ? 0 : 4;
+  static constexpr int kTM = TM, kSA = TM == 256 ? 2 : 3, kSB = kSA, kCW = TM == 256 ? 8 : 4;
+  static constexpr int kLoaders = TM == 256 ? 0 : 4;
   static constexpr bool kAMC = true;
   static constexpr bool kBNC = true;
   static constexpr bool kRowIdsInMemory = true;

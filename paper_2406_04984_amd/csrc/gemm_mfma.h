@@ -69,7 +69,7 @@ constexpr int kTN = 256, kTK = 64;
 #endif
 constexpr int kTMTok = MEFT_TOK_TM;    // tile rows of the token-major problems (groups of tokens against a block's rows)
 constexpr int kTMNeu = 128;            // tile rows of the router
-constexpr int kTMNeuW = MEFT_NEU_TM;   // tile rows of the neuron-major problems (dV, dK): 256, or 128
+constexpr int kTMNeuW = MEFT_NEU_TM;   // largest tile rows of the neuron-major problems (dV, dK): 256; 128 rules the larger tile out
 constexpr int kBSlotElems = kTN * kTK;                         // one B slot: 32 KB
 constexpr int kIdRingSlots = 4;                                // k tiles of gathered-row numbers kept per loader
 constexpr int kXcd = 8;

@@ -603,6 +603,37 @@ void launch_small_dvdk(const meft_shape& s, const DenseWs& w, const void* h, con
               static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
 }
 
+// Tile rows of the dV / dK contractions: 256 where that computes no more padded rows of the block than 128 would
+int neu_tile_rows(int block_rows) {
+  return kTMNeuW == 256 && (block_rows + 255) / 256 * 256 == (block_rows + 127) / 128 * 128 ? 256 : 128;
+}
+
+// One weight-gradient contraction (dV: A = A', X = dOut; dK: A = DS', X = h) over the groups of a tile schedule
+struct NeuArgs {
+  const uint16_t* A; int zrow; const uint16_t* X; uint16_t* G;
+  const int32_t *group_off, *tok_of_slot, *flag;
+  TokenSched sched;
+  int big_only, n_groups, bs, bsp, d;
+  uint64_t a_bytes, x_bytes;   // bytes readable from the lowest address of either operand
+};
+
+template <int TM>
+void launch_neu_tm(const char* name, const NeuArgs& a, hipStream_t st) {
+  ProbNeuTN<TM> pn{};
+  pn.A = a.A; pn.zrow = a.zrow; pn.X = a.X; pn.G = a.G;
+  pn.group_off = a.group_off; pn.tok_of_slot = a.tok_of_slot; pn.flag = a.flag;
+  pn.sched = a.sched; pn.big_only = a.big_only; pn.bs = a.bs; pn.bsp = a.bsp; pn.d = a.d;
+  set_gemm_extents(pn, a.a_bytes, a.x_bytes);
+  // every listed group has the same tiles; in the worst case one XCD holds all groups
+  const int64_t tiles = (int64_t)kXcd * a.n_groups * ((a.bs + TM - 1) / TM) * ((a.d + kTN - 1) / kTN);
+  launch_gemm_mfma(name, pn, (int)(tiles < (int64_t)INT32_MAX ? tiles : (int64_t)INT32_MAX), st);
+}
+
+void launch_neu(const char* name, const NeuArgs& a, hipStream_t st) {
+  if (neu_tile_rows(a.bs) == 256) launch_neu_tm<256>(name, a, st);
+  else launch_neu_tm<128>(name, a, st);
+}
+
 }  // namespace
 }  // namespace meft
 
@@ -750,20 +781,16 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
     MEFT_LAUNCH("compact_flags", compact_flags_kernel, dim3(n_chunks), dim3(256), 0, st, w.flag, s.N, w.chunk_cnt,
                 touched, n_touched);
     const TokenSched sched{w.sched_pairs, w.sched_len, sched_cap(s), sched_max_tiles(s)};
-    // every listed group has the same tiles; in the worst case one XCD holds all groups
-    const int64_t neu_tiles = (int64_t)kXcd * s.n_blocks * ((s.block_size + ProbNeuTN::kTM - 1) / ProbNeuTN::kTM) * ((s.d + kTN - 1) / kTN);
-    const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
-    ProbNeuTN pn{};
-    pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
-    pn.sched = sched; pn.bs = s.block_size; pn.bsp = bsp; pn.d = s.d;
     const int big_only = small_rows_of(s) > 0;   // the small groups: launch_small_* below
-    pn.big_only = big_only;
     const int n_ent = s.T * s.top_e;
+    NeuArgs pn{};
+    pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.flag;
+    pn.sched = sched; pn.big_only = big_only; pn.n_groups = s.n_blocks; pn.bs = s.block_size; pn.bsp = bsp; pn.d = s.d;
+    pn.a_bytes = (uint64_t)(1 + 2 * (uint64_t)n_ent) * bsp * 2; pn.x_bytes = (uint64_t)s.T * s.d * 2;
     // dV first: it needs neither K nor V (so it also runs while host-resident K, V are still on their way), and it
     // gathers the same dOut rows as the activation-gradient GEMM that follows it
     pn.A = w.Ap; pn.zrow = -1; pn.X = gg; pn.G = static_cast<uint16_t*>(dV);
-    set_gemm_extents(pn, (uint64_t)(1 + 2 * (uint64_t)n_ent) * bsp * 2, (uint64_t)s.T * s.d * 2);
-    launch_gemm_mfma("dV_gemm", pn, neu_grid, st);
+    launch_neu("dV_gemm", pn, st);
     if (wait_v && hipStreamWaitEvent(st, wait_v, 0) != hipSuccess) return MEFT_ERR_DEVICE;
     ProbTokKC<kTokMasked> pg{};
     pg.X = gg; pg.W = vv; pg.perm = w.perm; pg.group_off = w.group_off; pg.sched = sched;
@@ -783,7 +810,7 @@ static meft_status bwd_impl(const meft_shape& s, const void* h, const void* K, c
       launch_reduce_parts(s, w.part, w, dh, st);
     }
     pn.A = w.DS; pn.zrow = -(n_ent + 1); pn.X = hh; pn.G = static_cast<uint16_t*>(dK);
-    launch_gemm_mfma("dK_gemm", pn, neu_grid, st);
+    launch_neu("dK_gemm", pn, st);
     launch_small_dvdk(s, w, h, dOut, idx, act, dK, dV, st);
     return launch_status();
   }
@@ -916,16 +943,14 @@ meft_status meft_union_bwd(const meft_shape* shape, const void* h, const void* K
     launch_gemm_mfma("union_dh_gemm", ph, tile_bound(g.vs, (s.d + kTN - 1) / kTN), st);
     launch_reduce_parts(g.vs, w.part, w, dh, st);
   }
-  const int64_t neu_tiles = (int64_t)kXcd * g.nvb * ((g.vbs + ProbNeuTN::kTM - 1) / ProbNeuTN::kTM) * ((s.d + kTN - 1) / kTN);
-  const int neu_grid = (int)(neu_tiles < (int64_t)INT32_MAX ? neu_tiles : (int64_t)INT32_MAX);
-  ProbNeuTN pn{};
+  NeuArgs pn{};
   pn.group_off = w.group_off; pn.tok_of_slot = w.tok_of_slot; pn.flag = w.rowflag;
-  pn.sched = sched; pn.bs = g.vbs; pn.bsp = g.vbs; pn.d = s.d;
+  pn.sched = sched; pn.big_only = 0; pn.n_groups = g.nvb; pn.bs = g.vbs; pn.bsp = g.vbs; pn.d = s.d;
+  pn.a_bytes = (1 + 2 * (uint64_t)s.T * g.nvb) * g.vbs * 2; pn.x_bytes = (uint64_t)s.T * s.d * 2;
   pn.A = w.Ap; pn.zrow = -1; pn.X = gg; pn.G = w.dVc;
-  set_gemm_extents(pn, (1 + 2 * (uint64_t)s.T * g.nvb) * g.vbs * 2, (uint64_t)s.T * s.d * 2);
-  launch_gemm_mfma("union_dV_gemm", pn, neu_grid, st);
+  launch_neu("union_dV_gemm", pn, st);
   pn.A = w.DS; pn.zrow = -(s.T * g.nvb + 1); pn.X = hh; pn.G = w.dKc;
-  launch_gemm_mfma("union_dK_gemm", pn, neu_grid, st);
+  launch_neu("union_dK_gemm", pn, st);
   const int rows_grid = g.cap < 4096 ? g.cap : 4096;
   MEFT_LAUNCH("scatter_rows", scatter_rows_kernel, dim3(rows_grid), dim3(256), 0, st, w.dVc, S, n_S, s.N, s.d, g.cap,
               static_cast<uint16_t*>(dV));
