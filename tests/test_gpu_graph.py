@@ -9,11 +9,14 @@ from tests import parity as P
 pytestmark = pytest.mark.gpu
 
 CASES = [dict(T=150, d=72, n_blocks=6, block_size=40, top_e=2, top_k=12, dtype="f32", seed=1201),
-         dict(T=700, d=192, n_blocks=7, block_size=72, top_e=3, top_k=30, dtype="bf16", seed=1202)]
+         dict(T=700, d=192, n_blocks=7, block_size=72, top_e=3, top_k=30, dtype="bf16", seed=1202),
+         # unbalanced routing (blocks with a few tokens go to the per-pair kernels) and a backward on the forward's tables
+         dict(T=600, d=256, n_blocks=24, block_size=64, top_e=2, top_k=16, dtype="bf16", seed=1203, zipf_s=1.5,
+              reuse_fwd=True)]
 NAMES = ("block_idx", "block_score", "idx", "act", "out", "dh", "dK_bits", "dV_bits", "touched")
 
 
-@pytest.mark.parametrize("kw", CASES, ids=["gather_f32", "dense_bf16"])
+@pytest.mark.parametrize("kw", CASES, ids=["gather_f32", "dense_bf16", "dense_bf16_skewed_reuse"])
 def test_replays_of_a_captured_step_match_the_eager_step(kw):
     import torch
     t = synth.make_inputs(synth.small_case(**kw))
