@@ -77,8 +77,12 @@ def kernel_models(cfg, n_touched):
 STAGE_SYMBOL = {
     "router_gemm": "gemm_mfma_kernel<ProbRouter, true>", "score_gemm": "gemm_mfma_kernel<ProbTokKC<0>, true>",
     "dact_gemm": "gemm_mfma_kernel<ProbTokKC<1>, true>", "value_gemm": "gemm_mfma_kernel<ProbTokNC, true>",
-    "dh_gemm": "gemm_mfma_kernel<ProbTokNC, true>", "dV_gemm": "gemm_mfma_kernel<ProbNeuTN, true>",
-    "dK_gemm": "gemm_mfma_kernel<ProbNeuTN, true>", "topk_select": "topk_select_reg_kernel<16, true>", "reduce_parts": "reduce_parts_kernel<2>",
+    "dh_gemm": "gemm_mfma_kernel<ProbTokNC, true>",
+    # dV / dK: the tile height is chosen per shape (256 rows where the block fills them, else 128)
+    "dV_gemm": ("gemm_mfma_kernel<ProbNeuTN<256>, true>", "gemm_mfma_kernel<ProbNeuTN<128>, true>"),
+    "dK_gemm": ("gemm_mfma_kernel<ProbNeuTN<256>, true>", "gemm_mfma_kernel<ProbNeuTN<128>, true>"),
+    "topk_select": ("topk_select_reg_kernel<16, true>", "topk_select_reg_kernel<32, true>", "topk_select_reg_kernel<4, true>"),
+    "reduce_parts": "reduce_parts_kernel<2>",
 }
 GATHER_SCATTER = ("value_gemm", "dact_gemm", "dh_gemm", "dV_gemm", "dK_gemm", "gather_fwd", "gather_bwd", "seg_reduce")
 
@@ -90,9 +94,10 @@ def profiled_traffic(workload, stage):
     sym = STAGE_SYMBOL.get(stage)
     if sym is None or not os.path.exists(path):
         return None
+    syms = (sym,) if isinstance(sym, str) else sym
     for line in open(path):
         cells = [c.strip() for c in line.strip().strip("|").split("|")]
-        if len(cells) == 6 and cells[0] == sym:
+        if len(cells) == 6 and cells[0] in syms:
             try:
                 return {"read_bytes": float(cells[4]) * 1e6, "written_bytes": float(cells[5]) * 1e6,
                         "source": f"profiles/{workload}_all_kernels.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"}
