@@ -176,8 +176,8 @@ def main() -> int:
                          "other configurations); used for kernel profiles of the headline path alone")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; the layer shards by token across GPUs only on paper "
-              "(see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (sharding the layer by token over several GPUs is described, "
+              "not built). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
